@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the SSD-SGD update pipeline on one MI355X.
+
+A "step" is one ssd_step call: one full iteration of Algorithm 1 of the paper
+for the server and all K workers (server aggregate + momentum-SGD update, K GLU
+local updates, and -- every k-th iteration -- the Pull), as one fused launch.
+The workload is the VGG-16-shaped fp32 parameter set (138,357,544 elements in
+32 tensors, K = 8 workers, delay k = 4), with seeded synthetic weights and
+gradients already resident in HBM.  The timed region holds whole k-cycles so
+that every kind of iteration is weighted as in steady state.
+
+Prints ONE JSON line.  value = N / (seconds per step).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X, published
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
+# (FETCH_SIZE + WRITE_SIZE, scaled by what the same counters read on a copy of
+# known size); see profiles/.  None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes_per_element(K, kind, pre_action):
+    """fp32 bytes the method must move per model element in one iteration:
+    reads K gradients + w + mom (+ K local weights + pre_weight in the delay
+    stage), writes w + mom (+ K local weights, + pre_weight on init/refresh,
+    + K w_loc on a Pull iteration, + K local weights at the end of warm-up)."""
+    if kind == 0:
+        return 4 * K + 16
+    if kind == 1:
+        return 8 * K + 16
+    b = 12 * K + 20
+    if pre_action == 1:      # init: pre_weight written, not read
+        b += 0
+    elif pre_action == 2:    # refresh: pre_weight read and written
+        b += 4
+    if kind == 3:
+        b += 4 * K
+    return b
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="vgg16")
+    ap.add_argument("--chunk-elems", type=int, default=0)
+    ap.add_argument("--pool", type=int, default=2, help="distinct gradient sets cycled")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-elems", type=int, default=16 * 1024 * 1024)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is a one-GPU build (K workers are K resident sets of "
+                 "arrays on one GPU); --gpus %d is not supported, use --gpus 1" % args.gpus)
+
+    import numpy as np
+    import torch
+    from paper_2012_05396_amd import binding as B
+    from paper_2012_05396_amd import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+    wl = workloads.workload(args.workload)
+    numel = workloads.numels(wl.tensors)
+    N, T, K, k, W = sum(numel), len(numel), wl.K, wl.k, wl.W
+
+    wflat, offs = workloads.initial_weights(wl, device=dev)
+    weights = workloads.views(wflat, wl.tensors, offs)
+    P = args.pool
+    gsets = [workloads.gradient_set(wl, p, device=dev) for p in range(P)]
+    gviews = [[workloads.views(g, wl.tensors, offs) for g in gs] for gs in gsets]
+    tables = [B.GradTable(g) for g in gviews]
+
+    stream = torch.cuda.current_stream()
+    cfg = B.make_config(numel, K, k, W, wl.lr, wl.momentum, wl.wd, device=0,
+                        stream=stream.cuda_stream, chunk_elems=args.chunk_elems)
+    ctx = B.Context(cfg, weights)
+    view = ctx.ssd_get_state()
+
+    # untimed: the W SSGD iterations of the warm-up stage plus whole k-cycles
+    untimed = max(args.warmup, W)
+    if k > 0:
+        untimed = W + -(-(untimed - W) // k) * k
+    it = 0
+    for _ in range(untimed):
+        ctx.ssd_step(tables[it % P])
+        it += 1
+    torch.cuda.synchronize()
+
+    kinds, events = [], []
+    d = it - W
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        kind, pa = B.ssd_step_kind_of(it, W, k, d)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        ctx.ssd_step(tables[it % P])
+        e1.record(stream)
+        kinds.append((kind, pa))
+        events.append((e0, e1))
+        it += 1
+        d += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec_per_step = (t1 - t0) / args.steps
+    value = N / sec_per_step
+
+    # per-kind kernel durations from the HIP events of the timed region
+    per_kind = {}
+    for (kind, pa), (e0, e1) in zip(kinds, events):
+        per_kind.setdefault((kind, pa), []).append(e0.elapsed_time(e1))
+    names = {(0, 0): "warmup", (1, 0): "warmup_last", (2, 0): "delay_plain", (2, 1): "delay_init",
+             (2, 2): "delay_refresh", (3, 0): "delay_pull", (3, 1): "delay_init_pull",
+             (3, 2): "delay_refresh_pull"}
+    variants = {}
+    for key, ms in per_kind.items():
+        bpe = algorithmic_bytes_per_element(K, *key)
+        avg = sum(ms) / len(ms)
+        variants[names[key]] = {"launches": len(ms), "avg_ms": round(avg, 4), "min_ms": round(min(ms), 4),
+                                "bytes_per_elem": bpe,
+                                "algorithmic_GBps": round(bpe * N / (avg * 1e-3) / 1e9, 1)}
+    dom_key = (2, 0) if (2, 0) in per_kind else max(per_kind, key=lambda q: len(per_kind[q]))
+    dom = variants[names[dom_key]]
+    roofline = {"bound": "hbm", "kernel": "ssd_fused_kernel<K=%d> %s" % (K, names[dom_key]),
+                "achieved": dom["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(dom["algorithmic_GBps"] / HBM_PEAK_GBS, 4),
+                "algorithmic_bytes_per_launch": dom["bytes_per_elem"] * N,
+                "avg_launch_ms": dom["avg_ms"],
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)}
+    cycle_bytes = sum(algorithmic_bytes_per_element(K, *q) for q in kinds) * N / len(kinds)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl, N, K, k, W, wflat, gsets, offs, numel, args.cpu_sample_elems)
+
+    out = {
+        "metric": "param-elements updated/s per full SSD-SGD step",
+        "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": untimed,
+        "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s-shaped fp32 parameter set, N=%d elements in T=%d tensors, "
+                               "K=%d workers, delay k=%d, SSGD warm-up W=%d" % (wl.name, N, T, K, k, W),
+                   "chunk_elems": view.chunk_elems, "num_chunks": view.num_chunks,
+                   "gradient_sets_cycled": P, "lr": wl.lr, "momentum": wl.momentum, "wd": wl.wd},
+        "hbm_GBps_cycle_average_algorithmic": round(cycle_bytes / sec_per_step / 1e9, 1),
+        "hbm_frac_cycle_average": round(cycle_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS, 4),
+        "weight_elements_written_per_s": (K + 1) * value,
+        "variants": variants,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "context": "the paper reports no number for this path; its end-to-end speedups (up to 110% "
+                   "over SSGD) are on 4 x (4 x V100, no NVLink) + 56 Gb/s InfiniBand",
+    }
+    print(json.dumps(out))
+    ctx.close()
+
+
+def cpu_baseline(wl, N, K, k, W, wflat, gsets, offs, numel, sample_elems):
+    """Time the CPU oracle (binary32, GPU-order build, as it stands, one
+    thread) on the first `sample_elems` elements of the same workload for two
+    whole k-cycles of steps-delay iterations."""
+    import numpy as np
+    import torch
+    from oracle.ssd_oracle import Oracle
+    M = min(sample_elems, N)
+    # first M elements of the model in tensor order (paddings skipped)
+    idx_parts, left = [], M
+    for o, n in zip(offs, numel):
+        take = min(n, left)
+        if take <= 0:
+            break
+        idx_parts.append((o, take))
+        left -= take
+    def gather(flat):
+        return torch.cat([flat[o:o + n] for o, n in idx_parts]).cpu().numpy()
+    # weights have been updated by the GPU run; any values do for timing, but
+    # use fresh seeded initial weights of the same recipe for definiteness
+    from paper_2012_05396_amd import workloads
+    w0, _ = workloads.initial_weights(wl, device="cpu")
+    w0 = np.concatenate([w0[o:o + n].numpy() for o, n in idx_parts])
+    gh = [[gather(g) for g in gs] for gs in gsets]
+    o = Oracle(w0, K=K, k=k, W=W, lr=wl.lr, m=wl.momentum, wd=wl.wd, mode="f32")
+    for it in range(W):
+        o.step(gh[it % len(gh)])
+    steps = 2 * max(k, 1)
+    t0 = time.perf_counter()
+    for it in range(W, W + steps):
+        o.step(gh[it % len(gh)])
+    dt = (time.perf_counter() - t0) / steps
+    return {"value": M / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
+            "sample": "binary32 oracle (scalar C, gcc -O2 -ffp-contract=off, 1 thread) on the first "
+                      "%d elements of the same workload, %d steps-delay iterations (two k-cycles) "
+                      "after the %d warm-up iterations" % (M, steps, W),
+            "ms_per_step_on_sample": dt * 1e3, "host_cpus_visible": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,207 @@
+/*
+ * ssd.h -- C ABI of the SSD-SGD parameter-update pipeline for MI355X (gfx950).
+ *
+ * The library runs, on one GPU, the per-iteration update path of SSD-SGD
+ * ("Several Steps Delay SGD"): the parameter-server side (sum the K workers'
+ * gradients, apply momentum SGD with weight decay; Eq. (server) and the
+ * momentum rule of Sec. 3.2.1 of the paper) and the worker side (the GLU
+ * local update of Eq. (glu-update) with grad_sync of Sec. 3.3, scheduled by
+ * Algorithm 1 and Algorithm 2), over every layer tensor of a model.  The K
+ * workers are K resident sets of device arrays.
+ *
+ * Conventions for every entry point
+ *   - All data are IEEE binary32.  Pointers named "device" point to GPU global
+ *     memory of the configured device; all other pointers are host memory
+ *     that the library reads during the call only (it keeps no reference).
+ *   - Calls enqueue work on the stream given at ssd_init and return without
+ *     waiting for it.  Ordering against the caller's other GPU work is stream
+ *     order.  A context must be used from one host thread at a time.
+ *   - Return value: SSD_OK (0) or a negative SSD_E* code.  Arguments are
+ *     checked before anything is enqueued, so a failing call leaves the state
+ *     untouched.  ssd_last_error gives a message for the last failure.
+ *   - Nothing here throws or aborts across the boundary.
+ */
+#ifndef SSD_H
+#define SSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SSD_OK 0
+#define SSD_EINVAL (-1) /* null / negative / out-of-range argument            */
+#define SSD_EALIGN (-2) /* a device pointer is not 4-byte aligned, or the
+                           workspace is not 256-byte aligned                   */
+#define SSD_ENOMEM (-3) /* workspace too small, or host allocation failed     */
+#define SSD_EHIP (-4)   /* a HIP runtime call failed; text in ssd_last_error  */
+#define SSD_ESTATE (-5) /* call not allowed in the current schedule state     */
+
+#define SSD_MAX_WORKERS 16
+
+/* Kinds of iteration of the worker schedule (Algorithm 1 + Algorithm 2).
+ * d is the index of the steps-delay iteration (Alg. 2's loc_update). */
+enum ssd_step_kind {
+    SSD_STEP_WARMUP = 0,       /* SSGD iteration of the warm-up loop          */
+    SSD_STEP_WARMUP_LAST = 1,  /* last warm-up iteration: w'_i = w_t taken    */
+    SSD_STEP_DELAY = 2,        /* local update, no Pull                       */
+    SSD_STEP_DELAY_PULL = 3    /* local update, then Pull (d % k == k-1)      */
+};
+/* What Algorithm 2 does with pre_weight on a local update. */
+enum ssd_pre_action {
+    SSD_PRE_KEEP = 0,    /* grad_sync from pre_weight, pre_weight kept        */
+    SSD_PRE_INIT = 1,    /* d == 0: pre_weight initialised with w'            */
+    SSD_PRE_REFRESH = 2  /* d > 0 and d % k == 0: pre_weight = w' afterwards  */
+};
+
+typedef struct ssd_ctx ssd_ctx; /* opaque */
+
+/* Configuration.  Symbols follow Table 1 of the paper. */
+typedef struct {
+    int32_t num_workers;   /* K, 1..SSD_MAX_WORKERS                           */
+    int32_t delay_k;       /* k >= 0 delay steps; 0 = SSGD for ever           */
+    int32_t warmup_iters;  /* W >= 0 SSGD iterations before the steps-delay
+                              stage; Algorithm 1's wp + 1                     */
+    float lr;              /* global learning rate in the servers             */
+    float momentum;        /* m, momentum coefficient in the servers          */
+    float wd;              /* weight decay in the servers                     */
+    float lr_loc;          /* loc_lr; the paper uses 4 * lr (Sec. 4.1)        */
+    float alpha;           /* weight of the local gradient, 2.0 in Sec. 4.1   */
+    float beta;            /* weight of grad_sync, 0.5 in Sec. 4.1            */
+    float wd_loc;          /* weight decay inside Eq. (glu-update)            */
+    float rescale_grad;    /* factor on the sum of the K gradients; 1/K gives
+                              the averaged gradient of Table 1                */
+    int32_t num_tensors;   /* T >= 1 layer tensors                            */
+    const int64_t *numel;  /* host [T], elements per tensor, each >= 1        */
+    int32_t device;        /* HIP device ordinal                              */
+    void *stream;          /* hipStream_t; NULL = the default stream          */
+    int32_t chunk_elems;   /* elements per work chunk of the multi-tensor
+                              launch; 0 = choose; else a multiple of 1024     */
+} ssd_config;
+
+/* Device-side state, for inspection.  All arrays are "arena" arrays of
+ * arena_elems floats in which tensor t occupies
+ * [tensor_offset[t], tensor_offset[t] + numel[t]).  Worker i's copy of a
+ * per-worker array starts at base + i * arena_elems.  The pointers stay valid
+ * until ssd_destroy; the data they show are those of the work enqueued so
+ * far (synchronise the stream before reading). */
+typedef struct {
+    int64_t iterations;     /* ssd_step calls completed (Alg. 1's num)        */
+    int64_t local_updates;  /* d: local updates done by every worker          */
+    int32_t in_delay_stage; /* 0 while the next ssd_step is a warm-up step    */
+    int32_t has_local;      /* 1 once w'_i hold values                        */
+    int32_t w_loc_separate; /* 1: w_loc holds what the last Pull iteration
+                               broadcast; 0: w_loc_i is w'_i itself (or, in
+                               the warm-up stage, the global weight)          */
+    int32_t chunk_elems;
+    int64_t num_chunks;
+    int64_t arena_elems;
+    const int64_t *tensor_offset; /* host [T], owned by the context           */
+    float *mom;             /* device: momentum of the servers                */
+    float *pre;             /* device: pre_weight (one copy: Sec. 3.3 says all
+                               workers hold the same value)                   */
+    float *w_local;         /* device: w'_i, K arrays                         */
+    float *w_loc;           /* device: w_loc of the last Pull iteration, K
+                               arrays                                         */
+} ssd_state_view;
+
+/* Bytes of device workspace ssd_init needs for this configuration (state
+ * arrays, chunk table, pointer tables).  Host-only; touches no GPU. */
+int ssd_workspace_bytes(const ssd_config *cfg, size_t *bytes);
+
+/* Create a context (Algorithm 1, initialisation: global weight w_0 given,
+ * num = 0; momentum starts at 0).
+ *   weights   host [T] of device pointers: the global weights w_t, owned by
+ *             the caller, updated in place by every server update; must stay
+ *             valid until ssd_destroy.
+ *   workspace device memory of at least ssd_workspace_bytes, 256-byte
+ *             aligned, owned by the caller, used exclusively by the context
+ *             until ssd_destroy.
+ * Enqueues the clearing of the momentum (and, if warmup_iters == 0 and
+ * delay_k > 0, the copy w'_i = w_0).  On failure *out is NULL and
+ * ssd_last_error(NULL) has the reason. */
+int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace,
+             size_t workspace_bytes, ssd_ctx **out);
+
+/* Server side of one iteration (Eq. (server); momentum rule of Sec. 3.2.1):
+ *   S = g_0 + g_1 + ... + g_{K-1} (in this order), g = rescale_grad * S,
+ *   mom = m*mom - lr*(g + wd*w),  w = w + mom.
+ *   grads  host [K] of host [T] of device pointers, read-only gradients of
+ *          worker i, tensor t, numel[t] floats each.
+ * Does not advance the schedule. */
+int ssd_server_aggregate_update(ssd_ctx *ctx, const float *const *const *grads);
+
+/* One call of Algorithm 2 (GLU) for one worker, on its local weight w'_i:
+ *   grad_sync = (pre_weight - w') * (1-m)/(lr*k)            (Sec. 3.3)
+ *   pre_weight initialised with w' on the worker's first call, refreshed
+ *   with w' (value before this update) when loc_update > 0 and
+ *   loc_update % k == 0,
+ *   w' = w' - lr_loc*(alpha*g_i + wd_loc*w' + beta*grad_sync)  (Eq. glu-update)
+ *   grads_i  host [T] of device pointers, worker i's gradients.
+ * Needs delay_k > 0 and a worker that has pulled (SSD_ESTATE otherwise).
+ * Workers must advance in lock step: a worker may be at most one local update
+ * ahead of the slowest one (SSD_ESTATE otherwise); pre_weight is shared. */
+int ssd_worker_glu_update(ssd_ctx *ctx, int32_t worker, const float *const *grads_i);
+
+/* Pull of Algorithm 1 for one worker: w_loc_i = w'_i (the weights the next
+ * forward/backward uses), then w'_i = w_t (current global weight).  For a
+ * worker without local weights yet (the hand-over at the end of the warm-up
+ * stage) both become w_t. */
+int ssd_worker_pull(ssd_ctx *ctx, int32_t worker);
+
+/* One full iteration of Algorithm 1 for the server and all K workers, as one
+ * fused launch: warm-up iterations run the server update only (the last one
+ * also hands w_t to every w'_i); steps-delay iterations run the server update,
+ * the K GLU updates and, when d % k == k-1, the Pull.  Equivalent, bit for
+ * bit, to ssd_server_aggregate_update + K x ssd_worker_glu_update
+ * (+ K x ssd_worker_pull).  Needs all workers at the same local update count. */
+int ssd_step(ssd_ctx *ctx, const float *const *const *grads);
+
+/* Change the learning rates (schedules); grad_sync uses the new global lr
+ * from the next call on. */
+int ssd_set_lr(ssd_ctx *ctx, float lr, float lr_loc);
+
+/* Fill *out (host).  Does not synchronise. */
+int ssd_get_state(ssd_ctx *ctx, ssd_state_view *out);
+
+/* Message of the last failing call on this context; ctx == NULL: of the last
+ * failing ssd_init / ssd_workspace_bytes on this thread.  Never NULL. */
+const char *ssd_last_error(const ssd_ctx *ctx);
+
+/* Release host resources.  Work already enqueued must have finished or the
+ * caller must synchronise the stream first; workspace and weights are the
+ * caller's to free afterwards.  NULL is allowed. */
+void ssd_destroy(ssd_ctx *ctx);
+
+/* ---- host-only helpers (no GPU), used by the calls above ---------------- */
+
+/* Kind of iteration number `iteration` (0-based) and pre_weight action, for
+ * W warm-up iterations, delay k, and d local updates done so far.
+ * Returns an ssd_step_kind, or SSD_EINVAL. */
+int ssd_step_kind_of(int64_t iteration, int32_t warmup_iters, int32_t delay_k,
+                     int64_t local_updates, int32_t *pre_action);
+
+/* Work chunk of the multi-tensor launch: `len` elements of tensor `tensor`
+ * starting at element `offset` of that tensor. */
+typedef struct {
+    int32_t tensor;
+    int32_t len;
+    int64_t offset;
+} ssd_chunk;
+
+/* Split T tensors into chunks of at most chunk_elems elements (chunk_elems a
+ * positive multiple of 1024; 0 = the library's choice for this model).  Every
+ * element of every tensor lies in exactly one chunk; chunks of a tensor start
+ * at multiples of chunk_elems.  Writes up to `capacity` chunks to `out` (may
+ * be NULL to count only) and the total number to *count; *chunk_elems_used
+ * (may be NULL) receives the chunk size. */
+int ssd_plan_chunks(const int64_t *numel, int32_t num_tensors, int32_t chunk_elems,
+                    ssd_chunk *out, int64_t capacity, int64_t *count,
+                    int32_t *chunk_elems_used);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSD_H */

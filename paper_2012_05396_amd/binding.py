@@ -1,0 +1,223 @@
+"""Thin ctypes binding of libssd.so: same names as include/ssd.h, argument
+marshalling only.  Every step of the path runs in the library's HIP kernels;
+there is no CPU fallback -- without the built library, importing fails."""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libssd.so")
+
+SSD_OK, SSD_EINVAL, SSD_EALIGN, SSD_ENOMEM, SSD_EHIP, SSD_ESTATE = 0, -1, -2, -3, -4, -5
+SSD_MAX_WORKERS = 16
+SSD_STEP_WARMUP, SSD_STEP_WARMUP_LAST, SSD_STEP_DELAY, SSD_STEP_DELAY_PULL = 0, 1, 2, 3
+SSD_PRE_KEEP, SSD_PRE_INIT, SSD_PRE_REFRESH = 0, 1, 2
+
+
+class ssd_config(C.Structure):
+    _fields_ = [("num_workers", C.c_int32), ("delay_k", C.c_int32),
+                ("warmup_iters", C.c_int32),
+                ("lr", C.c_float), ("momentum", C.c_float), ("wd", C.c_float),
+                ("lr_loc", C.c_float), ("alpha", C.c_float),
+                ("beta", C.c_float), ("wd_loc", C.c_float),
+                ("rescale_grad", C.c_float),
+                ("num_tensors", C.c_int32),
+                ("numel", C.POINTER(C.c_int64)),
+                ("device", C.c_int32), ("stream", C.c_void_p),
+                ("chunk_elems", C.c_int32)]
+
+
+class ssd_state_view(C.Structure):
+    _fields_ = [("iterations", C.c_int64), ("local_updates", C.c_int64),
+                ("in_delay_stage", C.c_int32), ("has_local", C.c_int32),
+                ("w_loc_separate", C.c_int32), ("chunk_elems", C.c_int32),
+                ("num_chunks", C.c_int64), ("arena_elems", C.c_int64),
+                ("tensor_offset", C.POINTER(C.c_int64)),
+                ("mom", C.c_void_p), ("pre", C.c_void_p),
+                ("w_local", C.c_void_p), ("w_loc", C.c_void_p)]
+
+
+class ssd_chunk(C.Structure):
+    _fields_ = [("tensor", C.c_int32), ("len", C.c_int32), ("offset", C.c_int64)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libssd.so is not built (%s); run `python -m paper_2012_05396_amd.build` "
+            "or __graft_entry__.build()" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    P = C.POINTER
+    sigs = {
+        "ssd_workspace_bytes": (C.c_int, [P(ssd_config), P(C.c_size_t)]),
+        "ssd_init": (C.c_int, [P(ssd_config), P(C.c_void_p), C.c_void_p, C.c_size_t, P(C.c_void_p)]),
+        "ssd_server_aggregate_update": (C.c_int, [C.c_void_p, P(C.c_void_p)]),
+        "ssd_worker_glu_update": (C.c_int, [C.c_void_p, C.c_int32, P(C.c_void_p)]),
+        "ssd_worker_pull": (C.c_int, [C.c_void_p, C.c_int32]),
+        "ssd_step": (C.c_int, [C.c_void_p, P(C.c_void_p)]),
+        "ssd_set_lr": (C.c_int, [C.c_void_p, C.c_float, C.c_float]),
+        "ssd_get_state": (C.c_int, [C.c_void_p, P(ssd_state_view)]),
+        "ssd_last_error": (C.c_char_p, [C.c_void_p]),
+        "ssd_destroy": (None, [C.c_void_p]),
+        "ssd_step_kind_of": (C.c_int, [C.c_int64, C.c_int32, C.c_int32, C.c_int64, P(C.c_int32)]),
+        "ssd_plan_chunks": (C.c_int, [P(C.c_int64), C.c_int32, C.c_int32, P(ssd_chunk), C.c_int64,
+                                      P(C.c_int64), P(C.c_int32)]),
+    }
+    for name, (res, args) in sigs.items():
+        f = getattr(lib, name)
+        f.restype, f.argtypes = res, args
+    return lib
+
+
+lib = _load()
+
+
+class SsdError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("ssd error %d: %s" % (code, msg))
+        self.code = code
+
+
+def _check(rc, ctx=None):
+    if rc != SSD_OK:
+        raise SsdError(rc, (lib.ssd_last_error(ctx) or b"").decode())
+
+
+# ---- host-only helpers ----------------------------------------------------
+def ssd_step_kind_of(iteration, warmup_iters, delay_k, local_updates):
+    pa = C.c_int32(0)
+    kind = lib.ssd_step_kind_of(iteration, warmup_iters, delay_k, local_updates, C.byref(pa))
+    if kind < 0:
+        raise SsdError(kind, "bad argument")
+    return kind, pa.value
+
+
+def ssd_plan_chunks(numel, chunk_elems=0):
+    T = len(numel)
+    arr = (C.c_int64 * T)(*numel)
+    cnt, used = C.c_int64(0), C.c_int32(0)
+    _check(lib.ssd_plan_chunks(arr, T, chunk_elems, None, 0, C.byref(cnt), C.byref(used)))
+    out = (ssd_chunk * cnt.value)()
+    _check(lib.ssd_plan_chunks(arr, T, chunk_elems, out, cnt.value, C.byref(cnt), C.byref(used)))
+    return [(c.tensor, c.offset, c.len) for c in out], used.value
+
+
+def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=2.0, beta=0.5, wd_loc=None,
+                rescale_grad=None, device=0, stream=None, chunk_elems=0):
+    """ssd_config with the defaults of Sec. 4.1 of the paper (loc_lr = 4*lr,
+    alpha = 2, beta = 0.5) and the averaged gradient (1/K).  Returns the
+    struct; it keeps the numel array alive."""
+    import numpy as np
+    T = len(numel)
+    arr = (C.c_int64 * T)(*[int(n) for n in numel])
+    cfg = ssd_config(
+        num_workers=K, delay_k=k, warmup_iters=W, lr=lr, momentum=momentum, wd=wd,
+        lr_loc=float(np.float32(4.0) * np.float32(lr)) if lr_loc is None else lr_loc,
+        alpha=alpha, beta=beta, wd_loc=wd if wd_loc is None else wd_loc,
+        rescale_grad=float(np.float32(1.0 / K)) if rescale_grad is None else rescale_grad,
+        num_tensors=T, numel=arr, device=device,
+        stream=stream, chunk_elems=chunk_elems)
+    cfg._keep = arr
+    return cfg
+
+
+def ssd_workspace_bytes(cfg):
+    n = C.c_size_t(0)
+    _check(lib.ssd_workspace_bytes(C.byref(cfg), C.byref(n)))
+    return n.value
+
+
+class GradTable:
+    """Marshalled [K][T] table of device pointers for one set of gradient
+    tensors; build once per set and reuse (keeps the tensors alive)."""
+
+    def __init__(self, grads):
+        self.tensors = grads
+        K = len(grads)
+        self.rows = []
+        for row in grads:
+            self.rows.append((C.c_void_p * len(row))(*[t.data_ptr() for t in row]))
+        self.table = (C.c_void_p * K)(*[C.cast(r, C.c_void_p).value for r in self.rows])
+
+
+class Context:
+    """Owner of an ssd_ctx and of the torch-allocated workspace."""
+
+    def __init__(self, cfg, weights):
+        for t in weights:
+            assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+        self.cfg = cfg
+        self.weights = list(weights)
+        self.K, self.T = cfg.num_workers, cfg.num_tensors
+        self.numel = [cfg.numel[t] for t in range(self.T)]
+        nbytes = ssd_workspace_bytes(cfg)
+        dev = torch.device("cuda", cfg.device)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        wp = (C.c_void_p * self.T)(*[t.data_ptr() for t in weights])
+        h = C.c_void_p(None)
+        _check(lib.ssd_init(C.byref(cfg), wp, C.c_void_p(self._ws_ptr), nbytes, C.byref(h)))
+        self.h = h
+
+    def close(self):
+        if self.h:
+            lib.ssd_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @staticmethod
+    def _table(grads):
+        return grads if isinstance(grads, GradTable) else GradTable(grads)
+
+    def ssd_server_aggregate_update(self, grads):
+        g = self._table(grads)
+        _check(lib.ssd_server_aggregate_update(self.h, g.table), self.h)
+
+    def ssd_worker_glu_update(self, worker, grads_i):
+        row = (C.c_void_p * len(grads_i))(*[t.data_ptr() for t in grads_i])
+        _check(lib.ssd_worker_glu_update(self.h, worker, row), self.h)
+
+    def ssd_worker_pull(self, worker):
+        _check(lib.ssd_worker_pull(self.h, worker), self.h)
+
+    def ssd_step(self, grads):
+        g = self._table(grads)
+        _check(lib.ssd_step(self.h, g.table), self.h)
+
+    def ssd_set_lr(self, lr, lr_loc):
+        _check(lib.ssd_set_lr(self.h, lr, lr_loc), self.h)
+
+    def ssd_get_state(self):
+        v = ssd_state_view()
+        _check(lib.ssd_get_state(self.h, C.byref(v)), self.h)
+        return v
+
+    # views of the library-owned state as torch tensors (no copies) --------
+    def _arena(self, ptr, count):
+        """float32 view of `count` consecutive state arrays starting at ptr;
+        they live inside self.workspace."""
+        v = self.ssd_get_state()
+        off = ptr - self.workspace.data_ptr()
+        assert off >= 0 and off % 4 == 0
+        A = v.arena_elems
+        flat = self.workspace[off:off + 4 * A * count].view(torch.float32)
+        return flat.view(count, A), v
+
+    def state_tensors(self, which, worker=None):
+        """List of T per-tensor views of a state array: which in {"mom",
+        "pre", "w_local", "w_loc"}; per-worker arrays need `worker`."""
+        v = self.ssd_get_state()
+        ptr = getattr(v, which)
+        if ptr is None:
+            raise SsdError(SSD_ESTATE, "state array %s does not exist (delay_k = 0)" % which)
+        count = self.K if which in ("w_local", "w_loc") else 1
+        arena, v = self._arena(ptr, count)
+        row = arena[worker if count > 1 else 0]
+        return [row[v.tensor_offset[t]:v.tensor_offset[t] + self.numel[t]] for t in range(self.T)]

@@ -1,0 +1,65 @@
+"""Build libssd.so (HIP, gfx950 only) in-tree with hipcc.
+
+The fused kernel is compiled once per worker count K = 1..16 so that its
+worker loops unroll; the objects are built in parallel and linked into one
+shared library next to this file.
+"""
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libssd.so")
+MAX_K = 16
+
+# -ffp-contract=off: one rounding per written operation (the rounding sequence
+# is part of the library's contract).  Packed FP32 instructions stay off.
+FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
+         "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang",
+         "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
+
+
+def _run(cmd):
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT,
+                       text=True)
+    out = "\n".join(l for l in r.stdout.splitlines()
+                    if "packed-fp32-ops" not in l and l.strip())
+    if r.returncode != 0:
+        raise RuntimeError("build failed: %s\n%s" % (" ".join(cmd), out))
+    return out
+
+
+def build(jobs=None, verbose=False):
+    """Compile every source and link libssd.so.  Always recompiles."""
+    os.makedirs(OBJ, exist_ok=True)
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    units = []
+    for k in range(1, MAX_K + 1):
+        units.append((os.path.join(CSRC, "ssd_fused.hip"),
+                      os.path.join(OBJ, "ssd_fused_k%d.o" % k),
+                      ["-DSSD_K=%d" % k]))
+    units.append((os.path.join(CSRC, "ssd_aux.hip"),
+                  os.path.join(OBJ, "ssd_aux.o"), []))
+    units.append((os.path.join(CSRC, "ssd_host.hip"),
+                  os.path.join(OBJ, "ssd_host.o"), []))
+
+    def one(u):
+        src, obj, extra = u
+        return _run(["hipcc"] + FLAGS + extra + ["-c", src, "-o", obj])
+
+    with ThreadPoolExecutor(jobs) as ex:
+        for msg in ex.map(one, units):
+            if verbose and msg:
+                print(msg)
+    tmp = LIB + ".tmp%d" % os.getpid()
+    _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] +
+         [u[1] for u in units])
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

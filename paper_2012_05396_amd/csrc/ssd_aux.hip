@@ -1,0 +1,127 @@
+// Piecewise kernels: one worker's GLU update (Algorithm 2), one worker's Pull
+// (Algorithm 1), and a fill.  They walk the same chunk table as the fused
+// kernel and use the same element-wise rules, so a sequence of piecewise
+// calls gives the bits of the fused step.
+#include "ssd_device.h"
+
+template <int PRE, int VW>
+__device__ __forceinline__ void ssd_glu_elems(const ssd_hyper &h, cgfloat *gp, gfloat *wlp,
+                                              cgfloat *presrc, gfloat *predst, unsigned e)
+{
+    typedef ssd_vec<VW> V;
+    float g[VW], wl[VW], p[VW], r[VW];
+    V::ld(gp + e, g);
+    V::ld(wlp + e, wl);
+    if (PRE != SSD_PRE_INIT) V::ld(presrc + e, p);
+#pragma unroll
+    for (int v = 0; v < VW; ++v) {
+        float pv = (PRE == SSD_PRE_INIT) ? wl[v] : p[v];
+        r[v] = ssd_glu_elem(g[v], wl[v], pv, h);
+    }
+    if (PRE != SSD_PRE_KEEP) V::st(predst + e, wl);
+    V::st(wlp + e, r);
+}
+
+template <int PRE>
+__global__ __launch_bounds__(SSD_BLOCK) void ssd_glu_kernel(const ssd_glu_args a)
+{
+    const ssd_chunk c = a.chunks[blockIdx.x];
+    const ssd_tensor_desc td = a.tensors[c.tensor];
+    const float *g = a.gptr[c.tensor];
+    const bool vec = ssd_aligned16(g);
+    cgfloat *gp = ssd_global(g) + c.offset;
+    const int64_t ao = td.arena_off + c.offset;
+    gfloat *wlp = ssd_global(a.wl) + ao;
+    cgfloat *presrc = ssd_global(a.pre_src) + ao;
+    gfloat *predst = ssd_global(a.pre_dst) + ao;
+    const unsigned len = (unsigned)c.len, tid = threadIdx.x;
+    if (vec) {
+        const unsigned len4 = len & ~3u;
+        for (unsigned e = tid * 4; e < len4; e += SSD_BLOCK * 4)
+            ssd_glu_elems<PRE, 4>(a.h, gp, wlp, presrc, predst, e);
+        const unsigned e = len4 + tid;
+        if (e < len) ssd_glu_elems<PRE, 1>(a.h, gp, wlp, presrc, predst, e);
+    } else {
+        for (unsigned e = tid; e < len; e += SSD_BLOCK)
+            ssd_glu_elems<PRE, 1>(a.h, gp, wlp, presrc, predst, e);
+    }
+}
+
+hipError_t ssd_launch_glu(int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a)
+{
+    const dim3 grid(nchunks), block(SSD_BLOCK);
+    switch (pre_action) {
+    case SSD_PRE_KEEP: ssd_glu_kernel<SSD_PRE_KEEP><<<grid, block, 0, s>>>(a); break;
+    case SSD_PRE_INIT: ssd_glu_kernel<SSD_PRE_INIT><<<grid, block, 0, s>>>(a); break;
+    case SSD_PRE_REFRESH: ssd_glu_kernel<SSD_PRE_REFRESH><<<grid, block, 0, s>>>(a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// INIT: w'_i = w_t and w_loc_i = w_t.  Otherwise w_loc_i = w'_i, then w'_i = w_t.
+template <bool INIT, int VW>
+__device__ __forceinline__ void ssd_pull_elems(cgfloat *wp, gfloat *wlp, gfloat *wlocp, unsigned e)
+{
+    typedef ssd_vec<VW> V;
+    float w[VW], wl[VW];
+    V::ld(wp + e, w);
+    if (!INIT) {
+        V::ld(wlp + e, wl);
+        V::st(wlocp + e, wl);
+    } else {
+        V::st(wlocp + e, w);
+    }
+    V::st(wlp + e, w);
+}
+
+template <bool INIT>
+__global__ __launch_bounds__(SSD_BLOCK) void ssd_pull_kernel(const ssd_pull_args a)
+{
+    const ssd_chunk c = a.chunks[blockIdx.x];
+    const ssd_tensor_desc td = a.tensors[c.tensor];
+    const bool vec = ssd_aligned16(td.w);
+    cgfloat *wp = ssd_global((const float *)td.w) + c.offset;
+    const int64_t ao = td.arena_off + c.offset;
+    gfloat *wlp = ssd_global(a.wl) + ao, *wlocp = ssd_global(a.wloc) + ao;
+    const unsigned len = (unsigned)c.len, tid = threadIdx.x;
+    if (vec) {
+        const unsigned len4 = len & ~3u;
+        for (unsigned e = tid * 4; e < len4; e += SSD_BLOCK * 4)
+            ssd_pull_elems<INIT, 4>(wp, wlp, wlocp, e);
+        const unsigned e = len4 + tid;
+        if (e < len) ssd_pull_elems<INIT, 1>(wp, wlp, wlocp, e);
+    } else {
+        for (unsigned e = tid; e < len; e += SSD_BLOCK) ssd_pull_elems<INIT, 1>(wp, wlp, wlocp, e);
+    }
+}
+
+hipError_t ssd_launch_pull(int init, unsigned nchunks, hipStream_t s, const ssd_pull_args &a)
+{
+    const dim3 grid(nchunks), block(SSD_BLOCK);
+    if (init)
+        ssd_pull_kernel<true><<<grid, block, 0, s>>>(a);
+    else
+        ssd_pull_kernel<false><<<grid, block, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+// n is a multiple of 4 and p is 16-byte aligned (state arrays are padded).
+__global__ __launch_bounds__(SSD_BLOCK) void ssd_fill_zero_kernel(float *p, int64_t n4)
+{
+    typedef float v4 __attribute__((ext_vector_type(4)));
+    const v4 z = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t i = (int64_t)blockIdx.x * SSD_BLOCK + threadIdx.x; i < n4;
+         i += (int64_t)gridDim.x * SSD_BLOCK)
+        reinterpret_cast<v4 *>(p)[i] = z;
+}
+
+hipError_t ssd_launch_fill_zero(float *p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const int64_t n4 = n / 4;
+    int64_t blocks = (n4 + SSD_BLOCK - 1) / SSD_BLOCK;
+    if (blocks > 8192) blocks = 8192;
+    ssd_fill_zero_kernel<<<dim3((unsigned)blocks), dim3(SSD_BLOCK), 0, s>>>(p, n4);
+    return hipGetLastError();
+}

@@ -1,0 +1,137 @@
+// Internal to the HIP library: argument blocks, element-wise update rules and
+// vector load/store helpers shared by the fused and the piecewise kernels.
+//
+// The element-wise rules are written as one IEEE binary32 operation per
+// statement; the library is compiled with -ffp-contract=off so that none of
+// them is fused.  That fixes the rounding sequence:
+//   server (Eq. (server) + momentum rule of Sec. 3.2.1 of the SSD-SGD paper):
+//     S = g_0; S = S + g_i (i = 1..K-1); gh = S*rescale; t1 = wd*w;
+//     t2 = gh + t1; t3 = lr*t2; t4 = m*mom; mom' = t4 - t3; w' = w + mom'
+//   GLU (Eq. (glu-update), grad_sync of Sec. 3.3, descent sign):
+//     e = pre - wl; gs = e*c_sync; u1 = alpha*g; u2 = wd_loc*wl; u3 = u1 + u2;
+//     u4 = beta*gs; u5 = u3 + u4; u6 = lr_loc*u5; wl' = wl - u6
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ssd.h"
+
+#define SSD_BLOCK 256
+
+enum { SSD_STAGE_WARMUP = 0, SSD_STAGE_WARMUP_LAST = 1, SSD_STAGE_DELAY = 2 };
+
+struct ssd_tensor_desc {
+    float *w;          // global weight of this tensor (caller-owned)
+    int64_t arena_off; // element offset of the tensor inside every state array
+};
+
+struct ssd_hyper {
+    float rescale, lr, m, wd;                    // server
+    float c_sync, lr_loc, alpha, beta, wd_loc;   // worker
+};
+
+struct ssd_fused_args {
+    const ssd_chunk *chunks;
+    const ssd_tensor_desc *tensors;
+    const float *const *gptr; // [T][K] gradient pointers, worker index fastest
+    float *mom, *pre, *wl, *wloc;
+    int64_t A;                // elements per state array (worker stride)
+    ssd_hyper h;
+};
+
+struct ssd_glu_args {
+    const ssd_chunk *chunks;
+    const ssd_tensor_desc *tensors;
+    const float *const *gptr; // [T] gradient pointers of the one worker
+    const float *pre_src;     // pre_weight array to read
+    float *pre_dst;           // pre_weight array to write (init / refresh)
+    float *wl;                // this worker's w'
+    ssd_hyper h;
+};
+
+struct ssd_pull_args {
+    const ssd_chunk *chunks;
+    const ssd_tensor_desc *tensors;
+    float *wl, *wloc;         // this worker's arrays
+};
+
+__device__ __forceinline__ void ssd_server_elem(float S, float w, float mom, const ssd_hyper &h,
+                                                float &w_new, float &mom_new)
+{
+    float gh = S * h.rescale;
+    float t1 = h.wd * w;
+    float t2 = gh + t1;
+    float t3 = h.lr * t2;
+    float t4 = h.m * mom;
+    float mo = t4 - t3;
+    mom_new = mo;
+    w_new = w + mo;
+}
+
+__device__ __forceinline__ float ssd_glu_elem(float g, float wl, float pre, const ssd_hyper &h)
+{
+    float e = pre - wl;
+    float gs = e * h.c_sync;
+    float u1 = h.alpha * g;
+    float u2 = h.wd_loc * wl;
+    float u3 = u1 + u2;
+    float u4 = h.beta * gs;
+    float u5 = u3 + u4;
+    float u6 = h.lr_loc * u5;
+    return wl - u6;
+}
+
+// Pointers that come out of tables in memory are generic to the compiler;
+// casting them to the global address space gives global_load / global_store
+// with a scalar base and a 32-bit lane offset instead of flat accesses.
+typedef __attribute__((address_space(1))) float gfloat;
+typedef __attribute__((address_space(1))) const float cgfloat;
+static __device__ __forceinline__ gfloat *ssd_global(float *p) { return (gfloat *)p; }
+static __device__ __forceinline__ cgfloat *ssd_global(const float *p) { return (cgfloat *)p; }
+
+// VW-wide (1 or 4 floats) global loads and stores.  Every byte of the step is
+// touched once, so both are marked non-temporal.
+template <int VW> struct ssd_vec;
+template <> struct ssd_vec<1> {
+    static __device__ __forceinline__ void ld(cgfloat *p, float (&x)[1])
+    {
+        x[0] = __builtin_nontemporal_load(p);
+    }
+    static __device__ __forceinline__ void st(gfloat *p, const float (&x)[1])
+    {
+        __builtin_nontemporal_store(x[0], p);
+    }
+};
+template <> struct ssd_vec<4> {
+    typedef float v4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(1))) v4 gv4;
+    typedef __attribute__((address_space(1))) const v4 cgv4;
+    static __device__ __forceinline__ void ld(cgfloat *p, float (&x)[4])
+    {
+        v4 v = __builtin_nontemporal_load((cgv4 *)p);
+        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+    }
+    static __device__ __forceinline__ void st(gfloat *p, const float (&x)[4])
+    {
+        v4 v = {x[0], x[1], x[2], x[3]};
+        __builtin_nontemporal_store(v, (gv4 *)p);
+    }
+};
+
+static __device__ __forceinline__ bool ssd_aligned16(const void *p)
+{
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
+}
+
+// launchers, one translation unit each
+hipError_t ssd_launch_glu(int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a);
+hipError_t ssd_launch_pull(int init, unsigned nchunks, hipStream_t s, const ssd_pull_args &a);
+hipError_t ssd_launch_fill_zero(float *p, int64_t n, hipStream_t s);
+typedef hipError_t (*ssd_fused_launcher)(int stage, int pre_action, int pull, unsigned nchunks,
+                                         hipStream_t s, const ssd_fused_args &a);
+#define SSD_DECL_FUSED(k) \
+    hipError_t ssd_launch_fused_k##k(int, int, int, unsigned, hipStream_t, const ssd_fused_args &);
+SSD_DECL_FUSED(1) SSD_DECL_FUSED(2) SSD_DECL_FUSED(3) SSD_DECL_FUSED(4)
+SSD_DECL_FUSED(5) SSD_DECL_FUSED(6) SSD_DECL_FUSED(7) SSD_DECL_FUSED(8)
+SSD_DECL_FUSED(9) SSD_DECL_FUSED(10) SSD_DECL_FUSED(11) SSD_DECL_FUSED(12)
+SSD_DECL_FUSED(13) SSD_DECL_FUSED(14) SSD_DECL_FUSED(15) SSD_DECL_FUSED(16)

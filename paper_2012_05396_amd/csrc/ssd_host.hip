@@ -1,0 +1,609 @@
+// Host side of the SSD-SGD library: argument checks, the schedule of
+// Algorithm 1 / Algorithm 2 of the paper as a small state machine, the chunk
+// table of the multi-tensor launch, gradient-pointer tables, and the launches.
+// No arithmetic of the method runs here except the two configuration
+// constants c_sync = (1-m)/(lr*k) (Sec. 3.3) which is formed once per
+// learning-rate change in binary64 and rounded to binary32.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "ssd_device.h"
+
+namespace {
+
+thread_local char g_init_error[512] = "";
+
+void set_err(char *buf, size_t cap, const char *fmt, va_list ap) { vsnprintf(buf, cap, fmt, ap); }
+
+int fail_init(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    set_err(g_init_error, sizeof g_init_error, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+constexpr int64_t kTensorAlign = 64;  // elements: every tensor starts on 256 B
+constexpr size_t kWsAlign = 256;
+constexpr int kFusedSlots = 8;
+
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// A small cache of device-resident pointer tables keyed by content, so that a
+// caller cycling through a few sets of gradient buffers uploads each table
+// once.  Slot memory is reused in least-recently-used order; an event per slot
+// keeps the pinned staging copy alive until its upload has run.
+struct PtrCache {
+    int nslots = 0;
+    size_t len = 0;              // pointers per table
+    const float **dev = nullptr; // device [nslots][len] (inside the workspace)
+    const float **host = nullptr; // pinned [nslots][len]
+    std::vector<uint64_t> stamp;
+    std::vector<char> valid;
+    std::vector<hipEvent_t> ev;
+    uint64_t clock = 0;
+
+    hipError_t create(int n, size_t l, void *dev_mem)
+    {
+        nslots = n;
+        len = l;
+        dev = static_cast<const float **>(dev_mem);
+        stamp.assign(n, 0);
+        valid.assign(n, 0);
+        ev.assign(n, nullptr);
+        hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&host), sizeof(float *) * len * n,
+                                     hipHostMallocDefault);
+        if (e != hipSuccess) {
+            host = nullptr;
+            return e;
+        }
+        for (int i = 0; i < n; ++i) {
+            e = hipEventCreateWithFlags(&ev[i], hipEventDisableTiming);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    void destroy()
+    {
+        for (hipEvent_t e : ev)
+            if (e) (void)hipEventDestroy(e);
+        ev.clear();
+        if (host) (void)hipHostFree(host);
+        host = nullptr;
+    }
+    // key: len pointers.  Returns the device table holding them.
+    hipError_t get(const float *const *key, hipStream_t s, const float *const **out)
+    {
+        ++clock;
+        for (int i = 0; i < nslots; ++i)
+            if (valid[i] && std::memcmp(host + i * len, key, sizeof(float *) * len) == 0) {
+                stamp[i] = clock;
+                *out = dev + i * len;
+                return hipSuccess;
+            }
+        int lru = -1;
+        for (int i = 0; i < nslots && lru < 0; ++i)
+            if (!valid[i]) lru = i; // a free slot first
+        if (lru < 0) {
+            lru = 0;
+            for (int i = 1; i < nslots; ++i)
+                if (stamp[i] < stamp[lru]) lru = i;
+        }
+        hipError_t e;
+        if (valid[lru]) {
+            e = hipEventSynchronize(ev[lru]); // staging copy may still be queued
+            if (e != hipSuccess) return e;
+        }
+        valid[lru] = 0;
+        std::memcpy(host + lru * len, key, sizeof(float *) * len);
+        e = hipMemcpyAsync(dev + lru * len, host + lru * len, sizeof(float *) * len,
+                           hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) return e;
+        e = hipEventRecord(ev[lru], s);
+        if (e != hipSuccess) return e;
+        valid[lru] = 1;
+        stamp[lru] = clock;
+        *out = dev + lru * len;
+        return hipSuccess;
+    }
+};
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) return;
+        ok = true;
+        target = dev;
+    }
+    ~DeviceGuard()
+    {
+        if (ok && prev != target) (void)hipSetDevice(prev);
+    }
+    int target = -1;
+};
+
+struct Layout {
+    int64_t A = 0; // elements per state array
+    std::vector<int64_t> tensor_offset;
+    int32_t chunk_elems = 0;
+    int64_t num_chunks = 0;
+    size_t off_mom = 0, off_pre0 = 0, off_pre1 = 0, off_wl = 0, off_wloc = 0;
+    size_t off_chunks = 0, off_tensors = 0, off_gtab = 0, off_grow = 0;
+    int row_slots = 0;
+    size_t total = 0;
+};
+
+int check_config(const ssd_config *c)
+{
+    if (!c) return fail_init(SSD_EINVAL, "config is NULL");
+    if (c->num_workers < 1 || c->num_workers > SSD_MAX_WORKERS)
+        return fail_init(SSD_EINVAL, "num_workers = %d, must be 1..%d", c->num_workers, SSD_MAX_WORKERS);
+    if (c->delay_k < 0) return fail_init(SSD_EINVAL, "delay_k = %d, must be >= 0", c->delay_k);
+    if (c->warmup_iters < 0) return fail_init(SSD_EINVAL, "warmup_iters = %d, must be >= 0", c->warmup_iters);
+    if (c->num_tensors < 1) return fail_init(SSD_EINVAL, "num_tensors = %d, must be >= 1", c->num_tensors);
+    if (!c->numel) return fail_init(SSD_EINVAL, "numel is NULL");
+    for (int t = 0; t < c->num_tensors; ++t)
+        if (c->numel[t] < 1) return fail_init(SSD_EINVAL, "numel[%d] = %lld, must be >= 1", t, (long long)c->numel[t]);
+    if (c->delay_k > 0 && !(c->lr != 0.0f))
+        return fail_init(SSD_EINVAL, "lr = 0 with delay_k > 0: grad_sync divides by lr*k");
+    if (c->chunk_elems < 0 || c->chunk_elems % 1024 != 0)
+        return fail_init(SSD_EINVAL, "chunk_elems = %d, must be 0 or a positive multiple of 1024", c->chunk_elems);
+    if (c->device < 0) return fail_init(SSD_EINVAL, "device = %d", c->device);
+    return SSD_OK;
+}
+
+int make_layout(const ssd_config *c, Layout *L)
+{
+    const int T = c->num_tensors, K = c->num_workers;
+    L->tensor_offset.resize(T);
+    int64_t a = 0;
+    for (int t = 0; t < T; ++t) {
+        L->tensor_offset[t] = a;
+        a += (c->numel[t] + kTensorAlign - 1) / kTensorAlign * kTensorAlign;
+    }
+    L->A = a;
+    int rc = ssd_plan_chunks(c->numel, T, c->chunk_elems, nullptr, 0, &L->num_chunks, &L->chunk_elems);
+    if (rc != SSD_OK) return rc;
+    if (L->num_chunks > 0x7fffffffLL) return fail_init(SSD_EINVAL, "model needs %lld chunks, more than one launch holds", (long long)L->num_chunks);
+    size_t o = 0;
+    const size_t arr = round_up(sizeof(float) * (size_t)a, kWsAlign);
+    L->off_mom = o, o += arr;
+    if (c->delay_k > 0) {
+        L->off_pre0 = o, o += arr;
+        L->off_pre1 = o, o += arr;
+        L->off_wl = o, o += arr * K;
+        L->off_wloc = o, o += arr * K;
+    }
+    L->off_chunks = o, o += round_up(sizeof(ssd_chunk) * (size_t)L->num_chunks, kWsAlign);
+    L->off_tensors = o, o += round_up(sizeof(ssd_tensor_desc) * (size_t)T, kWsAlign);
+    L->off_gtab = o, o += round_up(sizeof(float *) * (size_t)T * K, kWsAlign) * kFusedSlots;
+    L->row_slots = std::max(8, 2 * K);
+    L->off_grow = o, o += round_up(sizeof(float *) * (size_t)T, kWsAlign) * L->row_slots;
+    L->total = o;
+    return SSD_OK;
+}
+
+} // namespace
+
+struct ssd_ctx {
+    ssd_config cfg;
+    std::vector<int64_t> numel;
+    Layout L;
+    hipStream_t stream = nullptr;
+    char *ws = nullptr;
+    float *mom = nullptr, *pre[2] = {nullptr, nullptr}, *wl = nullptr, *wloc = nullptr;
+    ssd_chunk *d_chunks = nullptr;
+    ssd_tensor_desc *d_tensors = nullptr;
+    PtrCache gtab, grow;
+    size_t gtab_stride = 0, grow_stride = 0;
+    ssd_hyper h;
+    int64_t it = 0;
+    std::vector<int64_t> loc_update;
+    std::vector<char> has_local, wloc_fresh;
+    int pre_cur = 0;      // which pre_weight array is current
+    int pre_written = 0;  // workers that have written the other one this round
+    std::vector<const float *> scratch; // [T*K] transposed pointer table
+    char err[512];
+
+    int fail(int code, const char *fmt, ...)
+    {
+        va_list ap;
+        va_start(ap, fmt);
+        set_err(err, sizeof err, fmt, ap);
+        va_end(ap);
+        return code;
+    }
+    int fail_hip(hipError_t e, const char *what)
+    {
+        return fail(SSD_EHIP, "%s: %s", what, hipGetErrorString(e));
+    }
+    void set_c_sync()
+    {
+        h.c_sync = cfg.delay_k > 0
+                       ? (float)((1.0 - (double)h.m) / ((double)h.lr * (double)cfg.delay_k))
+                       : 0.0f;
+    }
+    float *arr(float *base, int i) const { return base + (int64_t)i * stride_elems(); }
+    int64_t stride_elems() const { return (int64_t)(round_up(sizeof(float) * (size_t)L.A, kWsAlign) / sizeof(float)); }
+};
+
+extern "C" {
+
+int ssd_step_kind_of(int64_t iteration, int32_t W, int32_t k, int64_t d, int32_t *pre_action)
+{
+    if (iteration < 0 || W < 0 || k < 0 || d < 0) return SSD_EINVAL;
+    if (pre_action) *pre_action = SSD_PRE_KEEP;
+    if (k == 0 || iteration < W) // Alg. 1, warm-up loop (while num <= wp)
+        return (k > 0 && iteration == W - 1) ? SSD_STEP_WARMUP_LAST : SSD_STEP_WARMUP;
+    if (pre_action) // Alg. 2: initialise at the first local update, refresh every k
+        *pre_action = d == 0 ? SSD_PRE_INIT : (d % k == 0 ? SSD_PRE_REFRESH : SSD_PRE_KEEP);
+    return d % k == k - 1 ? SSD_STEP_DELAY_PULL : SSD_STEP_DELAY; // Alg. 1: Pull every k
+}
+
+int ssd_plan_chunks(const int64_t *numel, int32_t T, int32_t chunk_elems, ssd_chunk *out,
+                    int64_t capacity, int64_t *count, int32_t *used)
+{
+    if (!numel || T < 1 || !count) return fail_init(SSD_EINVAL, "ssd_plan_chunks: NULL argument or T < 1");
+    if (chunk_elems < 0 || chunk_elems % 1024 != 0)
+        return fail_init(SSD_EINVAL, "chunk_elems = %d, must be 0 or a positive multiple of 1024", chunk_elems);
+    int64_t N = 0;
+    for (int t = 0; t < T; ++t) {
+        if (numel[t] < 1) return fail_init(SSD_EINVAL, "numel[%d] = %lld, must be >= 1", t, (long long)numel[t]);
+        N += numel[t];
+    }
+    int64_t c = chunk_elems;
+    if (c == 0) { // enough chunks to fill 256 compute units several times over
+        c = 8192;
+        while (c > 1024 && N / c < 2048) c /= 2;
+    }
+    int64_t n = 0;
+    for (int t = 0; t < T; ++t)
+        for (int64_t off = 0; off < numel[t]; off += c, ++n)
+            if (out && n < capacity) {
+                out[n].tensor = t;
+                out[n].offset = off;
+                out[n].len = (int32_t)std::min<int64_t>(c, numel[t] - off);
+            }
+    *count = n;
+    if (used) *used = (int32_t)c;
+    return SSD_OK;
+}
+
+int ssd_workspace_bytes(const ssd_config *cfg, size_t *bytes)
+{
+    if (!bytes) return fail_init(SSD_EINVAL, "bytes is NULL");
+    int rc = check_config(cfg);
+    if (rc != SSD_OK) return rc;
+    Layout L;
+    rc = make_layout(cfg, &L);
+    if (rc != SSD_OK) return rc;
+    *bytes = L.total;
+    return SSD_OK;
+}
+
+void ssd_destroy(ssd_ctx *ctx)
+{
+    if (!ctx) return;
+    {
+        DeviceGuard g(ctx->cfg.device);
+        ctx->gtab.destroy();
+        ctx->grow.destroy();
+    }
+    delete ctx;
+}
+
+int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size_t workspace_bytes,
+             ssd_ctx **out)
+{
+    if (!out) return fail_init(SSD_EINVAL, "out is NULL");
+    *out = nullptr;
+    int rc = check_config(cfg);
+    if (rc != SSD_OK) return rc;
+    if (!weights) return fail_init(SSD_EINVAL, "weights is NULL");
+    if (!workspace) return fail_init(SSD_EINVAL, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace) % kWsAlign)
+        return fail_init(SSD_EALIGN, "workspace is not %zu-byte aligned", kWsAlign);
+    const int T = cfg->num_tensors, K = cfg->num_workers;
+    for (int t = 0; t < T; ++t) {
+        if (!weights[t]) return fail_init(SSD_EINVAL, "weights[%d] is NULL", t);
+        if (reinterpret_cast<uintptr_t>(weights[t]) % sizeof(float))
+            return fail_init(SSD_EALIGN, "weights[%d] is not 4-byte aligned", t);
+    }
+    ssd_ctx *c = new (std::nothrow) ssd_ctx;
+    if (!c) return fail_init(SSD_ENOMEM, "host allocation failed");
+    c->err[0] = 0;
+    c->cfg = *cfg;
+    c->numel.assign(cfg->numel, cfg->numel + T);
+    c->cfg.numel = c->numel.data();
+    rc = make_layout(&c->cfg, &c->L);
+    if (rc != SSD_OK) {
+        delete c;
+        return rc;
+    }
+    if (workspace_bytes < c->L.total) {
+        rc = fail_init(SSD_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, c->L.total);
+        delete c;
+        return rc;
+    }
+    c->stream = static_cast<hipStream_t>(cfg->stream);
+    c->ws = static_cast<char *>(workspace);
+    const Layout &L = c->L;
+    c->mom = reinterpret_cast<float *>(c->ws + L.off_mom);
+    if (cfg->delay_k > 0) {
+        c->pre[0] = reinterpret_cast<float *>(c->ws + L.off_pre0);
+        c->pre[1] = reinterpret_cast<float *>(c->ws + L.off_pre1);
+        c->wl = reinterpret_cast<float *>(c->ws + L.off_wl);
+        c->wloc = reinterpret_cast<float *>(c->ws + L.off_wloc);
+    }
+    c->d_chunks = reinterpret_cast<ssd_chunk *>(c->ws + L.off_chunks);
+    c->d_tensors = reinterpret_cast<ssd_tensor_desc *>(c->ws + L.off_tensors);
+    c->h.rescale = cfg->rescale_grad;
+    c->h.lr = cfg->lr;
+    c->h.m = cfg->momentum;
+    c->h.wd = cfg->wd;
+    c->h.lr_loc = cfg->lr_loc;
+    c->h.alpha = cfg->alpha;
+    c->h.beta = cfg->beta;
+    c->h.wd_loc = cfg->wd_loc;
+    c->set_c_sync();
+    c->loc_update.assign(K, 0);
+    c->has_local.assign(K, 0);
+    c->wloc_fresh.assign(K, 0);
+    c->scratch.resize((size_t)T * K);
+
+    DeviceGuard guard(cfg->device);
+    if (!guard.ok) {
+        rc = fail_init(SSD_EHIP, "cannot select device %d", cfg->device);
+        delete c;
+        return rc;
+    }
+    hipError_t e;
+#define SSD_INIT_HIP(call, what)                                                         \
+    do {                                                                                 \
+        e = (call);                                                                      \
+        if (e != hipSuccess) {                                                           \
+            rc = fail_init(SSD_EHIP, "%s: %s", what, hipGetErrorString(e));              \
+            ssd_destroy(c);                                                              \
+            return rc;                                                                   \
+        }                                                                                \
+    } while (0)
+    SSD_INIT_HIP(c->gtab.create(kFusedSlots, (size_t)T * K, c->ws + L.off_gtab), "pointer table (fused)");
+    // slots of the caches are packed at len pointers; the workspace reserves a
+    // rounded-up stride per slot, which is at least that
+    SSD_INIT_HIP(c->grow.create(L.row_slots, (size_t)T, c->ws + L.off_grow), "pointer table (rows)");
+
+    // chunk table and tensor descriptors: built on the host, uploaded once
+    std::vector<ssd_chunk> chunks((size_t)L.num_chunks);
+    int64_t n = 0;
+    ssd_plan_chunks(c->numel.data(), T, L.chunk_elems, chunks.data(), L.num_chunks, &n, nullptr);
+    std::vector<ssd_tensor_desc> descs(T);
+    for (int t = 0; t < T; ++t) {
+        descs[t].w = weights[t];
+        descs[t].arena_off = L.tensor_offset[t];
+    }
+    SSD_INIT_HIP(hipMemcpyAsync(c->d_chunks, chunks.data(), sizeof(ssd_chunk) * chunks.size(),
+                                hipMemcpyHostToDevice, c->stream), "upload chunk table");
+    SSD_INIT_HIP(hipMemcpyAsync(c->d_tensors, descs.data(), sizeof(ssd_tensor_desc) * descs.size(),
+                                hipMemcpyHostToDevice, c->stream), "upload tensor table");
+    SSD_INIT_HIP(hipStreamSynchronize(c->stream), "upload tables"); // sources are pageable locals
+    // momentum starts at zero (paddings included)
+    SSD_INIT_HIP(ssd_launch_fill_zero(c->mom, c->stride_elems(), c->stream), "clear momentum");
+    if (cfg->delay_k > 0) {
+        // paddings of the other state arrays are never read, but keep them defined
+        SSD_INIT_HIP(ssd_launch_fill_zero(c->pre[0], c->stride_elems() * (2 + 2 * (int64_t)K), c->stream), "clear state");
+        if (cfg->warmup_iters == 0) {
+            // Alg. 1 initialisation without a warm-up stage: every worker pulls w_0
+            for (int i = 0; i < K; ++i) {
+                ssd_pull_args a = {c->d_chunks, c->d_tensors, c->arr(c->wl, i), c->arr(c->wloc, i)};
+                SSD_INIT_HIP(ssd_launch_pull(1, (unsigned)L.num_chunks, c->stream, a), "initial pull");
+                c->has_local[i] = 1;
+            }
+        }
+    }
+#undef SSD_INIT_HIP
+    *out = c;
+    return SSD_OK;
+}
+
+static int check_grads(ssd_ctx *c, const float *const *const *grads)
+{
+    if (!grads) return c->fail(SSD_EINVAL, "grads is NULL");
+    const int T = c->cfg.num_tensors, K = c->cfg.num_workers;
+    for (int i = 0; i < K; ++i) {
+        if (!grads[i]) return c->fail(SSD_EINVAL, "grads[%d] is NULL", i);
+        for (int t = 0; t < T; ++t) {
+            const float *p = grads[i][t];
+            if (!p) return c->fail(SSD_EINVAL, "grads[%d][%d] is NULL", i, t);
+            if (reinterpret_cast<uintptr_t>(p) % sizeof(float))
+                return c->fail(SSD_EALIGN, "grads[%d][%d] is not 4-byte aligned", i, t);
+            c->scratch[(size_t)t * K + i] = p;
+        }
+    }
+    return SSD_OK;
+}
+
+static int launch_fused(ssd_ctx *c, int stage, int pre_action, int pull)
+{
+    static const ssd_fused_launcher table[SSD_MAX_WORKERS] = {
+        ssd_launch_fused_k1,  ssd_launch_fused_k2,  ssd_launch_fused_k3,  ssd_launch_fused_k4,
+        ssd_launch_fused_k5,  ssd_launch_fused_k6,  ssd_launch_fused_k7,  ssd_launch_fused_k8,
+        ssd_launch_fused_k9,  ssd_launch_fused_k10, ssd_launch_fused_k11, ssd_launch_fused_k12,
+        ssd_launch_fused_k13, ssd_launch_fused_k14, ssd_launch_fused_k15, ssd_launch_fused_k16};
+    const float *const *tab = nullptr;
+    hipError_t e = c->gtab.get(c->scratch.data(), c->stream, &tab);
+    if (e != hipSuccess) return c->fail_hip(e, "gradient pointer table");
+    ssd_fused_args a;
+    a.chunks = c->d_chunks;
+    a.tensors = c->d_tensors;
+    a.gptr = tab;
+    a.mom = c->mom;
+    a.pre = c->pre[c->pre_cur];
+    a.wl = c->wl;
+    a.wloc = c->wloc;
+    a.A = c->stride_elems();
+    a.h = c->h;
+    e = table[c->cfg.num_workers - 1](stage, pre_action, pull, (unsigned)c->L.num_chunks, c->stream, a);
+    if (e != hipSuccess) return c->fail_hip(e, "launch of the fused kernel");
+    return SSD_OK;
+}
+
+int ssd_server_aggregate_update(ssd_ctx *c, const float *const *const *grads)
+{
+    if (!c) return SSD_EINVAL;
+    int rc = check_grads(c, grads);
+    if (rc != SSD_OK) return rc;
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
+    return launch_fused(c, SSD_STAGE_WARMUP, SSD_PRE_KEEP, 0);
+}
+
+int ssd_step(ssd_ctx *c, const float *const *const *grads)
+{
+    if (!c) return SSD_EINVAL;
+    int rc = check_grads(c, grads);
+    if (rc != SSD_OK) return rc;
+    const int K = c->cfg.num_workers, k = c->cfg.delay_k, W = c->cfg.warmup_iters;
+    const int64_t d = c->loc_update[0];
+    for (int i = 1; i < K; ++i)
+        if (c->loc_update[i] != d)
+            return c->fail(SSD_ESTATE, "workers are at different local update counts (%lld vs %lld)",
+                           (long long)d, (long long)c->loc_update[i]);
+    if (c->pre_written != 0) return c->fail(SSD_ESTATE, "a piecewise local update round is unfinished");
+    int32_t pre_action = SSD_PRE_KEEP;
+    const int kind = ssd_step_kind_of(c->it, W, k, d, &pre_action);
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
+    if (kind == SSD_STEP_WARMUP || kind == SSD_STEP_WARMUP_LAST) {
+        rc = launch_fused(c, kind == SSD_STEP_WARMUP ? SSD_STAGE_WARMUP : SSD_STAGE_WARMUP_LAST,
+                          SSD_PRE_KEEP, 0);
+        if (rc != SSD_OK) return rc;
+        if (kind == SSD_STEP_WARMUP_LAST)
+            for (int i = 0; i < K; ++i) {
+                c->has_local[i] = 1;
+                c->wloc_fresh[i] = 0;
+                c->loc_update[i] = 0;
+            }
+    } else {
+        for (int i = 0; i < K; ++i)
+            if (!c->has_local[i]) return c->fail(SSD_ESTATE, "worker %d has no local weights", i);
+        const int pull = kind == SSD_STEP_DELAY_PULL;
+        rc = launch_fused(c, SSD_STAGE_DELAY, pre_action, pull);
+        if (rc != SSD_OK) return rc;
+        for (int i = 0; i < K; ++i) {
+            c->loc_update[i] = d + 1;
+            c->wloc_fresh[i] = (char)pull;
+        }
+    }
+    c->it += 1;
+    return SSD_OK;
+}
+
+int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const float *const *grads_i)
+{
+    if (!c) return SSD_EINVAL;
+    const int K = c->cfg.num_workers, k = c->cfg.delay_k, T = c->cfg.num_tensors;
+    if (worker < 0 || worker >= K) return c->fail(SSD_EINVAL, "worker = %d, must be 0..%d", worker, K - 1);
+    if (!grads_i) return c->fail(SSD_EINVAL, "grads_i is NULL");
+    for (int t = 0; t < T; ++t) {
+        if (!grads_i[t]) return c->fail(SSD_EINVAL, "grads_i[%d] is NULL", t);
+        if (reinterpret_cast<uintptr_t>(grads_i[t]) % sizeof(float))
+            return c->fail(SSD_EALIGN, "grads_i[%d] is not 4-byte aligned", t);
+    }
+    if (k == 0) return c->fail(SSD_ESTATE, "delay_k = 0: there is no steps-delay stage");
+    if (!c->has_local[worker]) return c->fail(SSD_ESTATE, "worker %d has no local weights yet (pull first)", worker);
+    const int64_t lu = c->loc_update[worker];
+    const int64_t dmin = *std::min_element(c->loc_update.begin(), c->loc_update.end());
+    if (lu != dmin)
+        return c->fail(SSD_ESTATE, "worker %d is at local update %lld but the slowest worker at %lld", worker,
+                       (long long)lu, (long long)dmin);
+    const int pre_action = lu == 0 ? SSD_PRE_INIT : (lu % k == 0 ? SSD_PRE_REFRESH : SSD_PRE_KEEP);
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
+    const float *const *tab = nullptr;
+    hipError_t e = c->grow.get(grads_i, c->stream, &tab);
+    if (e != hipSuccess) return c->fail_hip(e, "gradient pointer table");
+    ssd_glu_args a;
+    a.chunks = c->d_chunks;
+    a.tensors = c->d_tensors;
+    a.gptr = tab;
+    a.pre_src = c->pre[c->pre_cur];
+    a.pre_dst = c->pre[c->pre_cur ^ 1];
+    a.wl = c->arr(c->wl, worker);
+    a.h = c->h;
+    e = ssd_launch_glu(pre_action, (unsigned)c->L.num_chunks, c->stream, a);
+    if (e != hipSuccess) return c->fail_hip(e, "launch of the GLU kernel");
+    c->loc_update[worker] = lu + 1;
+    c->wloc_fresh[worker] = 0;
+    if (pre_action != SSD_PRE_KEEP && ++c->pre_written == K) {
+        c->pre_cur ^= 1; // every worker has written the same values to the other array
+        c->pre_written = 0;
+    }
+    return SSD_OK;
+}
+
+int ssd_worker_pull(ssd_ctx *c, int32_t worker)
+{
+    if (!c) return SSD_EINVAL;
+    const int K = c->cfg.num_workers;
+    if (worker < 0 || worker >= K) return c->fail(SSD_EINVAL, "worker = %d, must be 0..%d", worker, K - 1);
+    if (c->cfg.delay_k == 0) return c->fail(SSD_ESTATE, "delay_k = 0: workers keep no local weights");
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
+    ssd_pull_args a = {c->d_chunks, c->d_tensors, c->arr(c->wl, worker), c->arr(c->wloc, worker)};
+    hipError_t e = ssd_launch_pull(c->has_local[worker] ? 0 : 1, (unsigned)c->L.num_chunks, c->stream, a);
+    if (e != hipSuccess) return c->fail_hip(e, "launch of the pull kernel");
+    c->has_local[worker] = 1;
+    c->wloc_fresh[worker] = 1;
+    return SSD_OK;
+}
+
+int ssd_set_lr(ssd_ctx *c, float lr, float lr_loc)
+{
+    if (!c) return SSD_EINVAL;
+    if (c->cfg.delay_k > 0 && !(lr != 0.0f)) return c->fail(SSD_EINVAL, "lr = 0 with delay_k > 0: grad_sync divides by lr*k");
+    c->h.lr = lr;
+    c->h.lr_loc = lr_loc;
+    c->set_c_sync();
+    return SSD_OK;
+}
+
+int ssd_get_state(ssd_ctx *c, ssd_state_view *out)
+{
+    if (!c) return SSD_EINVAL;
+    if (!out) return c->fail(SSD_EINVAL, "out is NULL");
+    const int K = c->cfg.num_workers;
+    out->iterations = c->it;
+    out->local_updates = *std::min_element(c->loc_update.begin(), c->loc_update.end());
+    out->in_delay_stage = c->cfg.delay_k > 0 && c->it >= c->cfg.warmup_iters;
+    int all_local = 1, all_fresh = 1;
+    for (int i = 0; i < K; ++i) {
+        all_local &= c->has_local[i];
+        all_fresh &= c->wloc_fresh[i];
+    }
+    out->has_local = all_local;
+    out->w_loc_separate = all_local && all_fresh;
+    out->chunk_elems = c->L.chunk_elems;
+    out->num_chunks = c->L.num_chunks;
+    out->arena_elems = c->stride_elems();
+    out->tensor_offset = c->L.tensor_offset.data();
+    out->mom = c->mom;
+    out->pre = c->pre[c->pre_cur];
+    out->w_local = c->wl;
+    out->w_loc = c->wloc;
+    return SSD_OK;
+}
+
+const char *ssd_last_error(const ssd_ctx *c) { return c ? c->err : g_init_error; }
+
+} // extern "C"
