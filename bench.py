@@ -28,23 +28,22 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 MEASURED_TRAFFIC_BYTES = {}
 
 
-def algorithmic_bytes_per_element(K, kind, pre_action):
-    """fp32 bytes the method must move per model element in one iteration:
-    reads K gradients + w + mom (+ K local weights + pre_weight in the delay
-    stage), writes w + mom (+ K local weights, + pre_weight on init/refresh,
-    + K w_loc on a Pull iteration, + K local weights at the end of warm-up)."""
-    if kind == 0:
-        return 4 * K + 16
-    if kind == 1:
-        return 8 * K + 16
-    b = 12 * K + 20
-    if pre_action == 1:      # init: pre_weight written, not read
-        b += 0
-    elif pre_action == 2:    # refresh: pre_weight read and written
-        b += 4
-    if kind == 3:
-        b += 4 * K
-    return b
+def bytes_per_element(K, kind, pre_action, from_global):
+    """fp32 bytes per model element in one iteration, as (model, moved).
+
+    model: what the method must move if every array of Algorithm 1 / 2 is
+    kept explicitly -- reads K gradients + w + mom (+ K local weights +
+    pre_weight in the delay stage), writes w + mom (+ K local weights,
+    + pre_weight on init/refresh, + K w_loc and the K pulled weights on a Pull
+    iteration, + K local weights at the end of warm-up).
+    moved: what this library moves.  The hand-over at the end of warm-up and
+    the Pull are recorded instead of copied, and the iteration after them takes
+    w'_i from the global weight it loads anyway (from_global)."""
+    if kind in (0, 1):
+        return (4 * K + 16 + (4 * K if kind == 1 else 0), 4 * K + 16)
+    model = 12 * K + 20 + (4 if pre_action == 2 else 0) + (4 * K if kind == 3 else 0)
+    moved = 12 * K + 20 + (4 if pre_action == 2 else 0) - (4 * K if from_global else 0)
+    return (model, moved)
 
 
 def main():
@@ -56,6 +55,9 @@ def main():
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--pool", type=int, default=2, help="distinct gradient sets cycled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-copy-probe", action="store_true")
+    ap.add_argument("--grad-skew-elems", type=int, default=0,
+                    help="worker i's gradient buffer starts i*skew elements into its allocation")
     ap.add_argument("--cpu-sample-elems", type=int, default=16 * 1024 * 1024)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -77,7 +79,7 @@ def main():
     wflat, offs = workloads.initial_weights(wl, device=dev)
     weights = workloads.views(wflat, wl.tensors, offs)
     P = args.pool
-    gsets = [workloads.gradient_set(wl, p, device=dev) for p in range(P)]
+    gsets = [workloads.gradient_set(wl, p, device=dev, skew=args.grad_skew_elems) for p in range(P)]
     gviews = [[workloads.views(g, wl.tensors, offs) for g in gs] for gs in gsets]
     tables = [B.GradTable(g) for g in gviews]
 
@@ -97,18 +99,39 @@ def main():
         it += 1
     torch.cuda.synchronize()
 
+    # practical ceiling and counter calibration: a plain copy of known size
+    # (2^28 floats: 1 GiB read + 1 GiB written per launch), outside the timed region
+    probe = None
+    if not args.no_copy_probe:
+        n_probe = 1 << 28
+        src = torch.empty(n_probe, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            B.ssd_probe_copy(src, dst)
+        pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        pe[0].record(stream)
+        for _ in range(5):
+            B.ssd_probe_copy(src, dst)
+        pe[1].record(stream)
+        torch.cuda.synchronize()
+        ms = pe[0].elapsed_time(pe[1]) / 5
+        probe = {"kernel": "ssd_probe_copy_kernel", "bytes_per_launch": 8 * n_probe,
+                 "avg_ms": round(ms, 4), "GBps": round(8 * n_probe / (ms * 1e-3) / 1e9, 1)}
+        del src, dst
+
     kinds, events = [], []
     d = it - W
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         kind, pa = B.ssd_step_kind_of(it, W, k, d)
+        fg = ctx.ssd_get_state().w_local_is_global
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         e0.record(stream)
         ctx.ssd_step(tables[it % P])
         e1.record(stream)
-        kinds.append((kind, pa))
+        kinds.append((kind, pa, fg))
         events.append((e0, e1))
         it += 1
         d += 1
@@ -117,29 +140,34 @@ def main():
     sec_per_step = (t1 - t0) / args.steps
     value = N / sec_per_step
 
-    # per-kind kernel durations from the HIP events of the timed region
-    per_kind = {}
-    for (kind, pa), (e0, e1) in zip(kinds, events):
-        per_kind.setdefault((kind, pa), []).append(e0.elapsed_time(e1))
-    names = {(0, 0): "warmup", (1, 0): "warmup_last", (2, 0): "delay_plain", (2, 1): "delay_init",
-             (2, 2): "delay_refresh", (3, 0): "delay_pull", (3, 1): "delay_init_pull",
-             (3, 2): "delay_refresh_pull"}
+    # per-kernel durations from the HIP events of the timed region.  A Pull
+    # iteration runs the same kernel as a plain one (the Pull moves no data).
+    def kernel_name(kind, pa, fg):
+        if kind in (0, 1):
+            return "warmup"
+        return "delay_" + ("keep", "init", "refresh")[pa] + ("_from_global" if fg else "")
+    per_kernel = {}
+    for key, (e0, e1) in zip(kinds, events):
+        per_kernel.setdefault(kernel_name(*key), []).append((key, e0.elapsed_time(e1)))
     variants = {}
-    for key, ms in per_kind.items():
-        bpe = algorithmic_bytes_per_element(K, *key)
+    for name, lst in per_kernel.items():
+        ms = [x[1] for x in lst]
+        key = lst[0][0]
+        moved = bytes_per_element(K, key[0] if key[0] != 3 else 2, key[1], key[2])[1]
         avg = sum(ms) / len(ms)
-        variants[names[key]] = {"launches": len(ms), "avg_ms": round(avg, 4), "min_ms": round(min(ms), 4),
-                                "bytes_per_elem": bpe,
-                                "algorithmic_GBps": round(bpe * N / (avg * 1e-3) / 1e9, 1)}
-    dom_key = (2, 0) if (2, 0) in per_kind else max(per_kind, key=lambda q: len(per_kind[q]))
-    dom = variants[names[dom_key]]
-    roofline = {"bound": "hbm", "kernel": "ssd_fused_kernel<K=%d> %s" % (K, names[dom_key]),
-                "achieved": dom["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(dom["algorithmic_GBps"] / HBM_PEAK_GBS, 4),
-                "algorithmic_bytes_per_launch": dom["bytes_per_elem"] * N,
+        variants[name] = {"launches": len(ms), "avg_ms": round(avg, 4), "min_ms": round(min(ms), 4),
+                          "bytes_per_elem_moved": moved,
+                          "GBps": round(moved * N / (avg * 1e-3) / 1e9, 1)}
+    dom_name = "delay_keep" if "delay_keep" in variants else max(variants, key=lambda q: variants[q]["launches"])
+    dom = variants[dom_name]
+    roofline = {"bound": "hbm", "kernel": "ssd_fused_kernel<K=%d> %s" % (K, dom_name),
+                "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4),
+                "algorithmic_bytes_per_launch": dom["bytes_per_elem_moved"] * N,
                 "avg_launch_ms": dom["avg_ms"],
                 "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)}
-    cycle_bytes = sum(algorithmic_bytes_per_element(K, *q) for q in kinds) * N / len(kinds)
+    model_bytes = sum(bytes_per_element(K, *q)[0] for q in kinds) * N / len(kinds)
+    moved_bytes = sum(bytes_per_element(K, *q)[1] for q in kinds) * N / len(kinds)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -154,12 +182,15 @@ def main():
                                "K=%d workers, delay k=%d, SSGD warm-up W=%d" % (wl.name, N, T, K, k, W),
                    "chunk_elems": view.chunk_elems, "num_chunks": view.num_chunks,
                    "gradient_sets_cycled": P, "lr": wl.lr, "momentum": wl.momentum, "wd": wl.wd},
-        "hbm_GBps_cycle_average_algorithmic": round(cycle_bytes / sec_per_step / 1e9, 1),
-        "hbm_frac_cycle_average": round(cycle_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS, 4),
+        "bytes_per_elem_cycle_average": {"explicit_arrays_model": round(model_bytes / N, 2),
+                                         "moved": round(moved_bytes / N, 2)},
+        "hbm_GBps_cycle_average_moved": round(moved_bytes / sec_per_step / 1e9, 1),
+        "hbm_GBps_cycle_average_model": round(model_bytes / sec_per_step / 1e9, 1),
         "weight_elements_written_per_s": (K + 1) * value,
         "variants": variants,
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "copy_probe": probe,
         "context": "the paper reports no number for this path; its end-to-end speedups (up to 110% "
                    "over SSGD) are on 4 x (4 x V100, no NVLink) + 56 Gb/s InfiniBand",
     }

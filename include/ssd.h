@@ -56,6 +56,17 @@ enum ssd_pre_action {
     SSD_PRE_REFRESH = 2  /* d > 0 and d % k == 0: pre_weight = w' afterwards  */
 };
 
+/* Where the weights for the next forward/backward (w_loc, Alg. 1's Broadcast
+ * target) are found. */
+enum ssd_w_loc_where {
+    SSD_W_LOC_IS_GLOBAL = 0,  /* the global weights (warm-up stage, hand-over)  */
+    SSD_W_LOC_IN_W_LOCAL = 1, /* the w_local arrays: w_loc_i is w'_i itself, or
+                                 -- after a Pull iteration of ssd_step -- the
+                                 local weights as broadcast before the Pull    */
+    SSD_W_LOC_SEPARATE = 2    /* the w_loc arrays (after ssd_worker_pull or
+                                 ssd_materialize)                              */
+};
+
 typedef struct ssd_ctx ssd_ctx; /* opaque */
 
 /* Configuration.  Symbols follow Table 1 of the paper. */
@@ -91,10 +102,12 @@ typedef struct {
     int64_t iterations;     /* ssd_step calls completed (Alg. 1's num)        */
     int64_t local_updates;  /* d: local updates done by every worker          */
     int32_t in_delay_stage; /* 0 while the next ssd_step is a warm-up step    */
-    int32_t has_local;      /* 1 once w'_i hold values                        */
-    int32_t w_loc_separate; /* 1: w_loc holds what the last Pull iteration
-                               broadcast; 0: w_loc_i is w'_i itself (or, in
-                               the warm-up stage, the global weight)          */
+    int32_t has_local;      /* 1 once every worker has local weights w'_i     */
+    int32_t w_local_is_global; /* 1: every w'_i equals the global weight (after
+                               the end of warm-up or a Pull of ssd_step) and
+                               the w_local arrays do not hold it              */
+    int32_t w_loc_where;    /* where w_loc_i (what the next forward/backward
+                               uses) is: an ssd_w_loc_where value             */
     int32_t chunk_elems;
     int64_t num_chunks;
     int64_t arena_elems;
@@ -102,9 +115,8 @@ typedef struct {
     float *mom;             /* device: momentum of the servers                */
     float *pre;             /* device: pre_weight (one copy: Sec. 3.3 says all
                                workers hold the same value)                   */
-    float *w_local;         /* device: w'_i, K arrays                         */
-    float *w_loc;           /* device: w_loc of the last Pull iteration, K
-                               arrays                                         */
+    float *w_local;         /* device: w'_i, K arrays (see w_local_is_global)  */
+    float *w_loc;           /* device: K arrays, valid when w_loc_where says   */
 } ssd_state_view;
 
 /* Bytes of device workspace ssd_init needs for this configuration (state
@@ -130,7 +142,7 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace,
  *   mom = m*mom - lr*(g + wd*w),  w = w + mom.
  *   grads  host [K] of host [T] of device pointers, read-only gradients of
  *          worker i, tensor t, numel[t] floats each.
- * Does not advance the schedule. */
+ * Does not advance the schedule.  (Materialises first, see ssd_materialize.) */
 int ssd_server_aggregate_update(ssd_ctx *ctx, const float *const *const *grads);
 
 /* One call of Algorithm 2 (GLU) for one worker, on its local weight w'_i:
@@ -152,12 +164,21 @@ int ssd_worker_glu_update(ssd_ctx *ctx, int32_t worker, const float *const *grad
 int ssd_worker_pull(ssd_ctx *ctx, int32_t worker);
 
 /* One full iteration of Algorithm 1 for the server and all K workers, as one
- * fused launch: warm-up iterations run the server update only (the last one
- * also hands w_t to every w'_i); steps-delay iterations run the server update,
- * the K GLU updates and, when d % k == k-1, the Pull.  Equivalent, bit for
- * bit, to ssd_server_aggregate_update + K x ssd_worker_glu_update
- * (+ K x ssd_worker_pull).  Needs all workers at the same local update count. */
+ * fused launch: warm-up iterations run the server update only; steps-delay
+ * iterations run the server update and the K GLU updates.  The hand-over at
+ * the end of warm-up (w'_i = w_t) and the Pull when d % k == k-1 (w_loc_i =
+ * w'_i, then w'_i = w_t) move no data: the context records that every w'_i is
+ * the global weight (ssd_state_view.w_local_is_global) and the next iteration
+ * takes it from there.  In values, equivalent bit for bit to
+ * ssd_server_aggregate_update + K x ssd_worker_glu_update (+ K x
+ * ssd_worker_pull).  Needs all workers at the same local update count. */
 int ssd_step(ssd_ctx *ctx, const float *const *const *grads);
+
+/* Write out the state that ssd_step only records: if w_local_is_global, copy
+ * the broadcast local weights into the w_loc arrays and the global weight into
+ * every w'_i (afterwards w_local_is_global = 0, w_loc_where = SEPARATE).  The
+ * piecewise calls do this themselves when needed; no-op otherwise. */
+int ssd_materialize(ssd_ctx *ctx);
 
 /* Change the learning rates (schedules); grad_sync uses the new global lr
  * from the next call on. */
@@ -200,6 +221,15 @@ typedef struct {
 int ssd_plan_chunks(const int64_t *numel, int32_t num_tensors, int32_t chunk_elems,
                     ssd_chunk *out, int64_t capacity, int64_t *count,
                     int32_t *chunk_elems_used);
+
+/* ---- measurement aid ---------------------------------------------------- */
+
+/* Plain copy of n floats, device src -> device dst, on `stream`, with the same
+ * 128-bit streaming loads and stores the update kernels use: 4*n bytes read,
+ * 4*n bytes written, nothing else.  It is the known-size kernel against which
+ * hardware memory counters are scaled, and a practical bandwidth ceiling.
+ * n >= 0 and a multiple of 4; both pointers 16-byte aligned (SSD_EALIGN). */
+int ssd_probe_copy(const float *src, float *dst, int64_t n, void *stream);
 
 #ifdef __cplusplus
 }

@@ -7,12 +7,14 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libssd.so")
+# SSD_LIB_PATH selects another build of the same library (kernel experiments)
+LIB_PATH = os.environ.get("SSD_LIB_PATH") or os.path.join(_HERE, "libssd.so")
 
 SSD_OK, SSD_EINVAL, SSD_EALIGN, SSD_ENOMEM, SSD_EHIP, SSD_ESTATE = 0, -1, -2, -3, -4, -5
 SSD_MAX_WORKERS = 16
 SSD_STEP_WARMUP, SSD_STEP_WARMUP_LAST, SSD_STEP_DELAY, SSD_STEP_DELAY_PULL = 0, 1, 2, 3
 SSD_PRE_KEEP, SSD_PRE_INIT, SSD_PRE_REFRESH = 0, 1, 2
+SSD_W_LOC_IS_GLOBAL, SSD_W_LOC_IN_W_LOCAL, SSD_W_LOC_SEPARATE = 0, 1, 2
 
 
 class ssd_config(C.Structure):
@@ -31,7 +33,8 @@ class ssd_config(C.Structure):
 class ssd_state_view(C.Structure):
     _fields_ = [("iterations", C.c_int64), ("local_updates", C.c_int64),
                 ("in_delay_stage", C.c_int32), ("has_local", C.c_int32),
-                ("w_loc_separate", C.c_int32), ("chunk_elems", C.c_int32),
+                ("w_local_is_global", C.c_int32), ("w_loc_where", C.c_int32),
+                ("chunk_elems", C.c_int32),
                 ("num_chunks", C.c_int64), ("arena_elems", C.c_int64),
                 ("tensor_offset", C.POINTER(C.c_int64)),
                 ("mom", C.c_void_p), ("pre", C.c_void_p),
@@ -56,10 +59,12 @@ def _load():
         "ssd_worker_glu_update": (C.c_int, [C.c_void_p, C.c_int32, P(C.c_void_p)]),
         "ssd_worker_pull": (C.c_int, [C.c_void_p, C.c_int32]),
         "ssd_step": (C.c_int, [C.c_void_p, P(C.c_void_p)]),
+        "ssd_materialize": (C.c_int, [C.c_void_p]),
         "ssd_set_lr": (C.c_int, [C.c_void_p, C.c_float, C.c_float]),
         "ssd_get_state": (C.c_int, [C.c_void_p, P(ssd_state_view)]),
         "ssd_last_error": (C.c_char_p, [C.c_void_p]),
         "ssd_destroy": (None, [C.c_void_p]),
+        "ssd_probe_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
         "ssd_step_kind_of": (C.c_int, [C.c_int64, C.c_int32, C.c_int32, C.c_int64, P(C.c_int32)]),
         "ssd_plan_chunks": (C.c_int, [P(C.c_int64), C.c_int32, C.c_int32, P(ssd_chunk), C.c_int64,
                                       P(C.c_int64), P(C.c_int32)]),
@@ -103,6 +108,16 @@ def ssd_plan_chunks(numel, chunk_elems=0):
     return [(c.tensor, c.offset, c.len) for c in out], used.value
 
 
+def ssd_probe_copy(src, dst, stream=None):
+    """Plain device copy src -> dst (float32 tensors of equal size) with the
+    library's streaming loads and stores; a measurement aid."""
+    assert src.is_cuda and dst.is_cuda and src.numel() == dst.numel()
+    rc = lib.ssd_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel(),
+                            stream if stream is not None else torch.cuda.current_stream().cuda_stream)
+    if rc != SSD_OK:
+        raise SsdError(rc, "ssd_probe_copy: bad size or alignment")
+
+
 def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=2.0, beta=0.5, wd_loc=None,
                 rescale_grad=None, device=0, stream=None, chunk_elems=0):
     """ssd_config with the defaults of Sec. 4.1 of the paper (loc_lr = 4*lr,
@@ -115,7 +130,7 @@ def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=2.0, beta=0
         num_workers=K, delay_k=k, warmup_iters=W, lr=lr, momentum=momentum, wd=wd,
         lr_loc=float(np.float32(4.0) * np.float32(lr)) if lr_loc is None else lr_loc,
         alpha=alpha, beta=beta, wd_loc=wd if wd_loc is None else wd_loc,
-        rescale_grad=float(np.float32(1.0 / K)) if rescale_grad is None else rescale_grad,
+        rescale_grad=float(np.float32(1.0 / max(K, 1))) if rescale_grad is None else rescale_grad,
         num_tensors=T, numel=arr, device=device,
         stream=stream, chunk_elems=chunk_elems)
     cfg._keep = arr
@@ -190,6 +205,9 @@ class Context:
     def ssd_step(self, grads):
         g = self._table(grads)
         _check(lib.ssd_step(self.h, g.table), self.h)
+
+    def ssd_materialize(self):
+        _check(lib.ssd_materialize(self.h), self.h)
 
     def ssd_set_lr(self, lr, lr_loc):
         _check(lib.ssd_set_lr(self.h, lr, lr_loc), self.h)

@@ -32,8 +32,12 @@ def _run(cmd):
     return out
 
 
-def build(jobs=None, verbose=False):
-    """Compile every source and link libssd.so.  Always recompiles."""
+def build(jobs=None, verbose=False, defines=(), lib=None, obj_dir=None):
+    """Compile every source and link libssd.so.  Always recompiles.
+    `defines` ("-DX=1", ...), `lib` and `obj_dir` build an experimental
+    variant elsewhere."""
+    OBJ = obj_dir or globals()["OBJ"]
+    LIB = lib or globals()["LIB"]
     os.makedirs(OBJ, exist_ok=True)
     jobs = jobs or min(8, os.cpu_count() or 1)
     units = []
@@ -48,7 +52,7 @@ def build(jobs=None, verbose=False):
 
     def one(u):
         src, obj, extra = u
-        return _run(["hipcc"] + FLAGS + extra + ["-c", src, "-o", obj])
+        return _run(["hipcc"] + FLAGS + list(defines) + extra + ["-c", src, "-o", obj])
 
     with ThreadPoolExecutor(jobs) as ex:
         for msg in ex.map(one, units):

@@ -125,3 +125,28 @@ hipError_t ssd_launch_fill_zero(float *p, int64_t n, hipStream_t s)
     ssd_fill_zero_kernel<<<dim3((unsigned)blocks), dim3(SSD_BLOCK), 0, s>>>(p, n4);
     return hipGetLastError();
 }
+
+// Measurement aid: a plain copy with the library's own load/store helpers.
+__global__ __launch_bounds__(SSD_BLOCK) void ssd_probe_copy_kernel(const float *s, float *d, int64_t n)
+{
+    cgfloat *src = ssd_global(s);
+    gfloat *dst = ssd_global(d);
+    const int64_t e = ((int64_t)blockIdx.x * SSD_BLOCK + threadIdx.x) * 4;
+    if (e < n) {
+        float x[4];
+        ssd_vec<4>::ld(src + e, x);
+        ssd_vec<4>::st(dst + e, x);
+    }
+}
+
+extern "C" int ssd_probe_copy(const float *src, float *dst, int64_t n, void *stream)
+{
+    if (!src || !dst || n < 0 || n % 4) return SSD_EINVAL;
+    if (!ssd_aligned16_host(src) || !ssd_aligned16_host(dst)) return SSD_EALIGN;
+    if (n == 0) return SSD_OK;
+    const int64_t blocks = (n / 4 + SSD_BLOCK - 1) / SSD_BLOCK;
+    if (blocks > 0x7fffffffLL) return SSD_EINVAL;
+    ssd_probe_copy_kernel<<<dim3((unsigned)blocks), dim3(SSD_BLOCK), 0, static_cast<hipStream_t>(stream)>>>(
+        src, dst, n);
+    return hipGetLastError() == hipSuccess ? SSD_OK : SSD_EHIP;
+}

@@ -16,9 +16,18 @@
 
 #include "../../include/ssd.h"
 
+#ifndef SSD_BLOCK
 #define SSD_BLOCK 256
+#endif
+// non-temporal hints on the streaming accesses (build-time switches)
+#ifndef SSD_NT_LOAD
+#define SSD_NT_LOAD 1
+#endif
+#ifndef SSD_NT_STORE
+#define SSD_NT_STORE 1
+#endif
 
-enum { SSD_STAGE_WARMUP = 0, SSD_STAGE_WARMUP_LAST = 1, SSD_STAGE_DELAY = 2 };
+enum { SSD_STAGE_WARMUP = 0, SSD_STAGE_DELAY = 2 };
 
 struct ssd_tensor_desc {
     float *w;          // global weight of this tensor (caller-owned)
@@ -34,7 +43,7 @@ struct ssd_fused_args {
     const ssd_chunk *chunks;
     const ssd_tensor_desc *tensors;
     const float *const *gptr; // [T][K] gradient pointers, worker index fastest
-    float *mom, *pre, *wl, *wloc;
+    float *mom, *pre, *wl;
     int64_t A;                // elements per state array (worker stride)
     ssd_hyper h;
 };
@@ -95,11 +104,19 @@ template <int VW> struct ssd_vec;
 template <> struct ssd_vec<1> {
     static __device__ __forceinline__ void ld(cgfloat *p, float (&x)[1])
     {
+#if SSD_NT_LOAD
         x[0] = __builtin_nontemporal_load(p);
+#else
+        x[0] = *p;
+#endif
     }
     static __device__ __forceinline__ void st(gfloat *p, const float (&x)[1])
     {
+#if SSD_NT_STORE
         __builtin_nontemporal_store(x[0], p);
+#else
+        *p = x[0];
+#endif
     }
 };
 template <> struct ssd_vec<4> {
@@ -108,13 +125,21 @@ template <> struct ssd_vec<4> {
     typedef __attribute__((address_space(1))) const v4 cgv4;
     static __device__ __forceinline__ void ld(cgfloat *p, float (&x)[4])
     {
+#if SSD_NT_LOAD
         v4 v = __builtin_nontemporal_load((cgv4 *)p);
+#else
+        v4 v = *(cgv4 *)p;
+#endif
         x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
     }
     static __device__ __forceinline__ void st(gfloat *p, const float (&x)[4])
     {
         v4 v = {x[0], x[1], x[2], x[3]};
+#if SSD_NT_STORE
         __builtin_nontemporal_store(v, (gv4 *)p);
+#else
+        *(gv4 *)p = v;
+#endif
     }
 };
 
@@ -123,11 +148,16 @@ static __device__ __forceinline__ bool ssd_aligned16(const void *p)
     return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
 }
 
+static inline bool ssd_aligned16_host(const void *p)
+{
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
+}
+
 // launchers, one translation unit each
 hipError_t ssd_launch_glu(int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a);
 hipError_t ssd_launch_pull(int init, unsigned nchunks, hipStream_t s, const ssd_pull_args &a);
 hipError_t ssd_launch_fill_zero(float *p, int64_t n, hipStream_t s);
-typedef hipError_t (*ssd_fused_launcher)(int stage, int pre_action, int pull, unsigned nchunks,
+typedef hipError_t (*ssd_fused_launcher)(int stage, int pre_action, int from_global, unsigned nchunks,
                                          hipStream_t s, const ssd_fused_args &a);
 #define SSD_DECL_FUSED(k) \
     hipError_t ssd_launch_fused_k##k(int, int, int, unsigned, hipStream_t, const ssd_fused_args &);

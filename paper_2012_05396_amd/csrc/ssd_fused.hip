@@ -5,9 +5,11 @@
 // gradients, the global weight and the momentum exactly once, applies the
 // server update (Eq. (server), momentum rule of Sec. 3.2.1) and -- in the
 // steps-delay stage -- the K GLU updates of Algorithm 2 (Eq. (glu-update),
-// grad_sync of Sec. 3.3) on the K local weights, plus what Algorithm 1 does
-// at the end of the iteration (hand-over at the end of warm-up, Pull every k
-// iterations).  All K gradient loads and all K local-weight loads of a
+// grad_sync of Sec. 3.3) on the K local weights.  What Algorithm 1 does at the
+// end of an iteration moves no data here: after the hand-over at the end of
+// warm-up and after a Pull, every w'_i equals the global weight, so the host
+// only records that fact and the next launch (template flag FG) takes w'_i from
+// the global weight it loads anyway.  All K gradient loads and all K local-weight loads of a
 // thread are issued before the first use, as 128-bit accesses whenever every
 // pointer of the tensor is 16-byte aligned.
 //
@@ -18,10 +20,10 @@
 #error "compile with -DSSD_K=<number of workers>"
 #endif
 
-template <int K, int STAGE, int PRE, bool PULL, int VW>
+template <int K, int STAGE, int PRE, bool FG, int VW>
 __device__ __forceinline__ void ssd_fused_elems(const ssd_fused_args &a, cgfloat *const (&gp)[K],
                                                 gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp,
-                                                gfloat *wlocp, unsigned e)
+                                                unsigned e)
 {
     typedef ssd_vec<VW> V;
     float g[K][VW], w[VW], mo[VW], wl[K][VW], p[VW];
@@ -30,8 +32,10 @@ __device__ __forceinline__ void ssd_fused_elems(const ssd_fused_args &a, cgfloat
     V::ld(wp + e, w);
     V::ld(momp + e, mo);
     if (STAGE == SSD_STAGE_DELAY) {
+        if (!FG) {
 #pragma unroll
-        for (int i = 0; i < K; ++i) V::ld(wlp + i * a.A + e, wl[i]);
+            for (int i = 0; i < K; ++i) V::ld(wlp + i * a.A + e, wl[i]);
+        }
         if (PRE != SSD_PRE_INIT) V::ld(prep + e, p);
     }
 
@@ -46,34 +50,27 @@ __device__ __forceinline__ void ssd_fused_elems(const ssd_fused_args &a, cgfloat
     V::st(momp + e, mn);
     V::st(wp + e, wn);
 
-    if (STAGE == SSD_STAGE_WARMUP_LAST) {
-        // Alg. 1, last warm-up iteration: w'_{t,i} = w_t
-#pragma unroll
-        for (int i = 0; i < K; ++i) V::st(wlp + i * a.A + e, wn);
-    }
     if (STAGE == SSD_STAGE_DELAY) {
-        // Alg. 2: pre_weight takes w' as it was before this update
-        if (PRE != SSD_PRE_KEEP) V::st(prep + e, wl[0]);
+        // FG: every w'_i is the global weight as it stood before this
+        // iteration's server update (after a Pull, or at the end of warm-up),
+        // which is in registers already; the w' arrays are not read.
+        // Alg. 2: pre_weight takes w' as it was before this update.
+        if (PRE != SSD_PRE_KEEP) V::st(prep + e, FG ? w : wl[0]);
 #pragma unroll
         for (int i = 0; i < K; ++i) {
             float r[VW];
 #pragma unroll
             for (int v = 0; v < VW; ++v) {
-                float pv = (PRE == SSD_PRE_INIT) ? wl[i][v] : p[v];
-                r[v] = ssd_glu_elem(g[i][v], wl[i][v], pv, a.h);
+                const float wli = FG ? w[v] : wl[i][v];
+                const float pv = (PRE == SSD_PRE_INIT) ? wli : p[v];
+                r[v] = ssd_glu_elem(g[i][v], wli, pv, a.h);
             }
-            if (PULL) {
-                // Alg. 1: broadcast the updated w', then Pull w_t into w'
-                V::st(wlocp + i * a.A + e, r);
-                V::st(wlp + i * a.A + e, wn);
-            } else {
-                V::st(wlp + i * a.A + e, r);
-            }
+            V::st(wlp + i * a.A + e, r);
         }
     }
 }
 
-template <int K, int STAGE, int PRE, bool PULL>
+template <int K, int STAGE, int PRE, bool FG>
 __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const ssd_fused_args a)
 {
     const ssd_chunk c = a.chunks[blockIdx.x];
@@ -89,43 +86,41 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const ssd_fused_ar
     gfloat *wp = ssd_global(td.w) + c.offset;
     const int64_t ao = td.arena_off + c.offset;
     gfloat *momp = ssd_global(a.mom) + ao, *prep = ssd_global(a.pre) + ao;
-    gfloat *wlp = ssd_global(a.wl) + ao, *wlocp = ssd_global(a.wloc) + ao;
+    gfloat *wlp = ssd_global(a.wl) + ao;
     const unsigned len = (unsigned)c.len;
     const unsigned tid = threadIdx.x;
 
     if (vec) {
         const unsigned len4 = len & ~3u;
         for (unsigned e = tid * 4; e < len4; e += SSD_BLOCK * 4)
-            ssd_fused_elems<K, STAGE, PRE, PULL, 4>(a, gp, wp, momp, prep, wlp, wlocp, e);
+            ssd_fused_elems<K, STAGE, PRE, FG, 4>(a, gp, wp, momp, prep, wlp, e);
         const unsigned e = len4 + tid;
-        if (e < len) ssd_fused_elems<K, STAGE, PRE, PULL, 1>(a, gp, wp, momp, prep, wlp, wlocp, e);
+        if (e < len) ssd_fused_elems<K, STAGE, PRE, FG, 1>(a, gp, wp, momp, prep, wlp, e);
     } else {
         for (unsigned e = tid; e < len; e += SSD_BLOCK)
-            ssd_fused_elems<K, STAGE, PRE, PULL, 1>(a, gp, wp, momp, prep, wlp, wlocp, e);
+            ssd_fused_elems<K, STAGE, PRE, FG, 1>(a, gp, wp, momp, prep, wlp, e);
     }
 }
 
 #define SSD_CAT2(a, b) a##b
 #define SSD_CAT(a, b) SSD_CAT2(a, b)
 
-hipError_t SSD_CAT(ssd_launch_fused_k, SSD_K)(int stage, int pre_action, int pull, unsigned nchunks,
+hipError_t SSD_CAT(ssd_launch_fused_k, SSD_K)(int stage, int pre_action, int from_global, unsigned nchunks,
                                                hipStream_t s, const ssd_fused_args &a)
 {
     const dim3 grid(nchunks), block(SSD_BLOCK);
-#define SSD_GO(ST, PR, PU)                                                         \
+#define SSD_GO(ST, PR, FG)                                                         \
     do {                                                                           \
-        ssd_fused_kernel<SSD_K, ST, PR, PU><<<grid, block, 0, s>>>(a);             \
+        ssd_fused_kernel<SSD_K, ST, PR, FG><<<grid, block, 0, s>>>(a);             \
         return hipGetLastError();                                                  \
     } while (0)
     if (stage == SSD_STAGE_WARMUP) SSD_GO(SSD_STAGE_WARMUP, SSD_PRE_KEEP, false);
-    if (stage == SSD_STAGE_WARMUP_LAST) SSD_GO(SSD_STAGE_WARMUP_LAST, SSD_PRE_KEEP, false);
     if (stage == SSD_STAGE_DELAY) {
-        if (pre_action == SSD_PRE_KEEP && !pull) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_KEEP, false);
-        if (pre_action == SSD_PRE_KEEP && pull) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_KEEP, true);
-        if (pre_action == SSD_PRE_INIT && !pull) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_INIT, false);
-        if (pre_action == SSD_PRE_INIT && pull) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_INIT, true);
-        if (pre_action == SSD_PRE_REFRESH && !pull) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_REFRESH, false);
-        if (pre_action == SSD_PRE_REFRESH && pull) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_REFRESH, true);
+        if (pre_action == SSD_PRE_KEEP && !from_global) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_KEEP, false);
+        if (pre_action == SSD_PRE_INIT && !from_global) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_INIT, false);
+        if (pre_action == SSD_PRE_INIT && from_global) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_INIT, true);
+        if (pre_action == SSD_PRE_REFRESH && !from_global) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_REFRESH, false);
+        if (pre_action == SSD_PRE_REFRESH && from_global) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_REFRESH, true);
     }
     return hipErrorInvalidValue;
 }

@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -134,7 +135,8 @@ struct DeviceGuard {
 };
 
 struct Layout {
-    int64_t A = 0; // elements per state array
+    int64_t A = 0;      // elements of one state array that hold tensors
+    int64_t stride = 0; // elements from one state array to the next (>= A)
     std::vector<int64_t> tensor_offset;
     int32_t chunk_elems = 0;
     int64_t num_chunks = 0;
@@ -177,7 +179,10 @@ int make_layout(const ssd_config *c, Layout *L)
     if (rc != SSD_OK) return rc;
     if (L->num_chunks > 0x7fffffffLL) return fail_init(SSD_EINVAL, "model needs %lld chunks, more than one launch holds", (long long)L->num_chunks);
     size_t o = 0;
-    const size_t arr = round_up(sizeof(float) * (size_t)a, kWsAlign);
+    size_t pad = 0;
+    if (const char *e = getenv("SSD_STRIDE_PAD_BYTES")) pad = (size_t)atoll(e);
+    const size_t arr = round_up(sizeof(float) * (size_t)a + pad, kWsAlign);
+    L->stride = (int64_t)(arr / sizeof(float));
     L->off_mom = o, o += arr;
     if (c->delay_k > 0) {
         L->off_pre0 = o, o += arr;
@@ -211,6 +216,11 @@ struct ssd_ctx {
     int64_t it = 0;
     std::vector<int64_t> loc_update;
     std::vector<char> has_local, wloc_fresh;
+    // After the hand-over at the end of warm-up and after a Pull of the fused
+    // step, every w'_i equals the global weight; that is recorded here instead
+    // of being written K times.  wl_holds_wloc: the w' arrays then still hold
+    // the local weights that were broadcast as w_loc before the Pull.
+    bool wl_is_global = false, wl_holds_wloc = false;
     int pre_cur = 0;      // which pre_weight array is current
     int pre_written = 0;  // workers that have written the other one this round
     std::vector<const float *> scratch; // [T*K] transposed pointer table
@@ -235,7 +245,7 @@ struct ssd_ctx {
                        : 0.0f;
     }
     float *arr(float *base, int i) const { return base + (int64_t)i * stride_elems(); }
-    int64_t stride_elems() const { return (int64_t)(round_up(sizeof(float) * (size_t)L.A, kWsAlign) / sizeof(float)); }
+    int64_t stride_elems() const { return L.stride; }
 };
 
 extern "C" {
@@ -404,11 +414,8 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
         SSD_INIT_HIP(ssd_launch_fill_zero(c->pre[0], c->stride_elems() * (2 + 2 * (int64_t)K), c->stream), "clear state");
         if (cfg->warmup_iters == 0) {
             // Alg. 1 initialisation without a warm-up stage: every worker pulls w_0
-            for (int i = 0; i < K; ++i) {
-                ssd_pull_args a = {c->d_chunks, c->d_tensors, c->arr(c->wl, i), c->arr(c->wloc, i)};
-                SSD_INIT_HIP(ssd_launch_pull(1, (unsigned)L.num_chunks, c->stream, a), "initial pull");
-                c->has_local[i] = 1;
-            }
+            for (int i = 0; i < K; ++i) c->has_local[i] = 1;
+            c->wl_is_global = true;
         }
     }
 #undef SSD_INIT_HIP
@@ -433,7 +440,7 @@ static int check_grads(ssd_ctx *c, const float *const *const *grads)
     return SSD_OK;
 }
 
-static int launch_fused(ssd_ctx *c, int stage, int pre_action, int pull)
+static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
 {
     static const ssd_fused_launcher table[SSD_MAX_WORKERS] = {
         ssd_launch_fused_k1,  ssd_launch_fused_k2,  ssd_launch_fused_k3,  ssd_launch_fused_k4,
@@ -450,12 +457,36 @@ static int launch_fused(ssd_ctx *c, int stage, int pre_action, int pull)
     a.mom = c->mom;
     a.pre = c->pre[c->pre_cur];
     a.wl = c->wl;
-    a.wloc = c->wloc;
     a.A = c->stride_elems();
     a.h = c->h;
-    e = table[c->cfg.num_workers - 1](stage, pre_action, pull, (unsigned)c->L.num_chunks, c->stream, a);
+    e = table[c->cfg.num_workers - 1](stage, pre_action, from_global, (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the fused kernel");
     return SSD_OK;
+}
+
+// Write out what the flags wl_is_global / wl_holds_wloc stand for: w_loc_i takes
+// the broadcast local weights (or the global weight), w'_i the global weight.
+// Needed before anything changes the global weight outside the fused step.
+static int materialize(ssd_ctx *c)
+{
+    if (!c->wl_is_global) return SSD_OK;
+    const int K = c->cfg.num_workers;
+    for (int i = 0; i < K; ++i) {
+        ssd_pull_args a = {c->d_chunks, c->d_tensors, c->arr(c->wl, i), c->arr(c->wloc, i)};
+        hipError_t e = ssd_launch_pull(c->wl_holds_wloc ? 0 : 1, (unsigned)c->L.num_chunks, c->stream, a);
+        if (e != hipSuccess) return c->fail_hip(e, "launch of the pull kernel");
+        c->wloc_fresh[i] = 1;
+    }
+    c->wl_is_global = c->wl_holds_wloc = false;
+    return SSD_OK;
+}
+
+int ssd_materialize(ssd_ctx *c)
+{
+    if (!c) return SSD_EINVAL;
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
+    return materialize(c);
 }
 
 int ssd_server_aggregate_update(ssd_ctx *c, const float *const *const *grads)
@@ -465,6 +496,8 @@ int ssd_server_aggregate_update(ssd_ctx *c, const float *const *const *grads)
     if (rc != SSD_OK) return rc;
     DeviceGuard guard(c->cfg.device);
     if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
+    rc = materialize(c); // the global weight is about to change
+    if (rc != SSD_OK) return rc;
     return launch_fused(c, SSD_STAGE_WARMUP, SSD_PRE_KEEP, 0);
 }
 
@@ -485,24 +518,34 @@ int ssd_step(ssd_ctx *c, const float *const *const *grads)
     DeviceGuard guard(c->cfg.device);
     if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
     if (kind == SSD_STEP_WARMUP || kind == SSD_STEP_WARMUP_LAST) {
-        rc = launch_fused(c, kind == SSD_STEP_WARMUP ? SSD_STAGE_WARMUP : SSD_STAGE_WARMUP_LAST,
-                          SSD_PRE_KEEP, 0);
+        rc = launch_fused(c, SSD_STAGE_WARMUP, SSD_PRE_KEEP, 0);
         if (rc != SSD_OK) return rc;
-        if (kind == SSD_STEP_WARMUP_LAST)
+        if (kind == SSD_STEP_WARMUP_LAST) {
+            // Alg. 1: w'_{t,i} = w_t for every worker -- recorded, not copied
             for (int i = 0; i < K; ++i) {
                 c->has_local[i] = 1;
                 c->wloc_fresh[i] = 0;
                 c->loc_update[i] = 0;
             }
+            c->wl_is_global = true;
+            c->wl_holds_wloc = false;
+        }
     } else {
         for (int i = 0; i < K; ++i)
             if (!c->has_local[i]) return c->fail(SSD_ESTATE, "worker %d has no local weights", i);
-        const int pull = kind == SSD_STEP_DELAY_PULL;
-        rc = launch_fused(c, SSD_STAGE_DELAY, pre_action, pull);
+        if (c->wl_is_global && pre_action == SSD_PRE_KEEP) {
+            rc = materialize(c); // only after piecewise calls moved the schedule
+            if (rc != SSD_OK) return rc;
+        }
+        rc = launch_fused(c, SSD_STAGE_DELAY, pre_action, c->wl_is_global ? 1 : 0);
         if (rc != SSD_OK) return rc;
+        // Alg. 1, Pull iteration: the updated w' were broadcast (they stay in
+        // the w' arrays as w_loc) and w' = w_t from now on -- recorded only
+        const bool pull = kind == SSD_STEP_DELAY_PULL;
+        c->wl_is_global = c->wl_holds_wloc = pull;
         for (int i = 0; i < K; ++i) {
             c->loc_update[i] = d + 1;
-            c->wloc_fresh[i] = (char)pull;
+            c->wloc_fresh[i] = 0;
         }
     }
     c->it += 1;
@@ -530,6 +573,8 @@ int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const float *const *grads_
     const int pre_action = lu == 0 ? SSD_PRE_INIT : (lu % k == 0 ? SSD_PRE_REFRESH : SSD_PRE_KEEP);
     DeviceGuard guard(c->cfg.device);
     if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
+    int rc = materialize(c);
+    if (rc != SSD_OK) return rc;
     const float *const *tab = nullptr;
     hipError_t e = c->grow.get(grads_i, c->stream, &tab);
     if (e != hipSuccess) return c->fail_hip(e, "gradient pointer table");
@@ -560,6 +605,8 @@ int ssd_worker_pull(ssd_ctx *c, int32_t worker)
     if (c->cfg.delay_k == 0) return c->fail(SSD_ESTATE, "delay_k = 0: workers keep no local weights");
     DeviceGuard guard(c->cfg.device);
     if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
+    int rc = materialize(c);
+    if (rc != SSD_OK) return rc;
     ssd_pull_args a = {c->d_chunks, c->d_tensors, c->arr(c->wl, worker), c->arr(c->wloc, worker)};
     hipError_t e = ssd_launch_pull(c->has_local[worker] ? 0 : 1, (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the pull kernel");
@@ -592,7 +639,13 @@ int ssd_get_state(ssd_ctx *c, ssd_state_view *out)
         all_fresh &= c->wloc_fresh[i];
     }
     out->has_local = all_local;
-    out->w_loc_separate = all_local && all_fresh;
+    out->w_local_is_global = c->wl_is_global ? 1 : 0;
+    if (!all_local || (c->wl_is_global && !c->wl_holds_wloc))
+        out->w_loc_where = SSD_W_LOC_IS_GLOBAL;
+    else if (c->wl_is_global || !all_fresh)
+        out->w_loc_where = SSD_W_LOC_IN_W_LOCAL;
+    else
+        out->w_loc_where = SSD_W_LOC_SEPARATE;
     out->chunk_elems = c->L.chunk_elems;
     out->num_chunks = c->L.num_chunks;
     out->arena_elems = c->stride_elems();

@@ -162,7 +162,7 @@ def initial_weights(wl, device="cpu", align=64, shift=0):
     return flat, offs
 
 
-def gradient_set(wl, set_index, device="cpu", align=64, shift=0):
+def gradient_set(wl, set_index, device="cpu", align=64, shift=0, skew=0):
     """Gradients of all K workers for one iteration: a list of K flat fp32
     buffers laid out like the weights.  Each tensor ~ N(0, grad_sigma),
     optionally times 1/sqrt(fan_in) per layer, optionally with a seeded
@@ -171,7 +171,9 @@ def gradient_set(wl, set_index, device="cpu", align=64, shift=0):
     out = []
     for i in range(wl.K):
         g = _gen(device, (wl.seed * 1000003 + 7919 * (set_index + 1)) * 64 + i)
-        flat = torch.empty(total, dtype=torch.float32, device=device)
+        # skew: worker i's buffer starts i*skew elements into its allocation,
+        # so that the K buffers do not share one address alignment
+        flat = torch.empty(total + i * skew, dtype=torch.float32, device=device)[i * skew:]
         flat.normal_(0.0, wl.grad_sigma, generator=g)
         if wl.grad_fan_in_scale:
             for t, o in zip(wl.tensors, offs):

@@ -61,13 +61,22 @@ class Model:
             o += v.numel()
 
 
-def effective_w_loc(ctx, model, i):
-    """What worker i's next forward/backward would use: the w_loc array after
-    a Pull iteration, else w'_i itself, else (warm-up stage) the global weight."""
+def effective_w_local(ctx, model, i):
+    """w'_i: the w_local array, or the global weight when the context records
+    that every w'_i equals it."""
     v = ctx.ssd_get_state()
-    if v.w_loc_separate:
+    if v.w_local_is_global:
+        return cat(model.weights)
+    return cat(ctx.state_tensors("w_local", i))
+
+
+def effective_w_loc(ctx, model, i):
+    """What worker i's next forward/backward would use."""
+    from paper_2012_05396_amd import binding as B
+    v = ctx.ssd_get_state()
+    if v.w_loc_where == B.SSD_W_LOC_SEPARATE:
         return cat(ctx.state_tensors("w_loc", i))
-    if v.has_local:
+    if v.w_loc_where == B.SSD_W_LOC_IN_W_LOCAL:
         return cat(ctx.state_tensors("w_local", i))
     return cat(model.weights)
 
@@ -107,7 +116,7 @@ def compare_state(ctx, model, o, exact=True, tol=1e-5, where=""):
         return
     if v.has_local:
         for i in range(K):
-            chk("w_local[%d]" % i, cat(ctx.state_tensors("w_local", i)), o.wl[i])
+            chk("w_local[%d]" % i, effective_w_local(ctx, model, i), o.wl[i])
         if o.d > 0:
             chk("pre", cat(ctx.state_tensors("pre")), o.pre[0])
             for i in range(1, K):

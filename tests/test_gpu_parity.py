@@ -6,7 +6,8 @@ import numpy as np
 import pytest
 import torch
 
-from ssd_harness import Model, bits, cat, compare_state, effective_w_loc, run_schedule
+from ssd_harness import (Model, bits, cat, compare_state, effective_w_loc, effective_w_local,
+                         run_schedule)
 
 pytestmark = pytest.mark.gpu
 
@@ -120,8 +121,8 @@ def test_piecewise_calls_equal_fused_step():
             assert np.array_equal(bits(cat(ca.state_tensors(nm))), bits(cat(cb.state_tensors(nm)))), (it, nm)
         if it >= W - 1:
             for i in range(K):
-                assert np.array_equal(bits(cat(ca.state_tensors("w_local", i))),
-                                      bits(cat(cb.state_tensors("w_local", i)))), (it, i)
+                assert np.array_equal(bits(effective_w_local(ca, ma, i)),
+                                      bits(effective_w_local(cb, mb, i))), (it, i)
                 assert np.array_equal(bits(effective_w_loc(ca, ma, i)),
                                       bits(effective_w_loc(cb, mb, i))), (it, i)
         compare_state(cb, mb, o, exact=True, where="piecewise it=%d" % it)
@@ -146,9 +147,79 @@ def test_homogeneity_power_of_two_scaling():
                                       stream=torch.cuda.current_stream().cuda_stream), m.weights)
         for it in range(W + 2 * k + 1):
             ctx.ssd_step(m.g_dev[it % 3])
+        ctx.ssd_materialize()
         torch.cuda.synchronize()
         res.append([cat(m.weights) / scale, cat(ctx.state_tensors("mom")) / scale] +
                    [cat(ctx.state_tensors("w_local", i)) / scale for i in range(K)])
         ctx.close()
     for a, b in zip(*res):
         assert np.array_equal(bits(a), bits(b))
+
+
+def test_materialize_writes_out_recorded_state():
+    """After a Pull iteration of ssd_step the w' arrays hold w_loc and w' is
+    recorded as global; ssd_materialize must produce explicit arrays equal to
+    the oracle's, and later fused steps must continue unchanged."""
+    print("case: materialize", flush=True)
+    from oracle.ssd_oracle import Oracle
+    from paper_2012_05396_amd import binding as B
+    numel, K, k, W = ODD, 3, 2, 1
+    m = Model(numel, K, seed=21)
+    ctx = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, chunk_elems=1024,
+                                  stream=torch.cuda.current_stream().cuda_stream), m.weights)
+    o = Oracle(m.w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=1e-4, mode="f32")
+    for it in range(W + 3 * k):
+        ctx.ssd_step(m.g_dev[it % 3])
+        o.step(m.g_host[it % 3])
+        v = ctx.ssd_get_state()
+        if it == W - 1:
+            assert v.w_local_is_global == 1 and v.w_loc_where == B.SSD_W_LOC_IS_GLOBAL
+        elif (it - W) % k == k - 1:
+            assert v.w_local_is_global == 1 and v.w_loc_where == B.SSD_W_LOC_IN_W_LOCAL
+        else:
+            assert v.w_local_is_global == 0 and v.w_loc_where == B.SSD_W_LOC_IN_W_LOCAL
+        if it in (W - 1, W + 1, W + 2):          # hand-over, a Pull iteration, a plain one
+            ctx.ssd_materialize()
+            v = ctx.ssd_get_state()
+            assert v.w_local_is_global == 0
+            torch.cuda.synchronize()
+            for i in range(K):
+                assert np.array_equal(bits(cat(ctx.state_tensors("w_local", i))), bits(o.wl[i])), it
+                if v.w_loc_where == B.SSD_W_LOC_SEPARATE:
+                    assert np.array_equal(bits(cat(ctx.state_tensors("w_loc", i))), bits(o.wloc[i])), it
+        compare_state(ctx, m, o, exact=True, where="materialize it=%d" % it)
+    ctx.close()
+
+
+def test_mixed_fused_and_piecewise_iterations():
+    """Alternate ssd_step with piecewise iterations inside one schedule; every
+    hand-over between the two (recorded Pull -> explicit arrays) must keep the
+    state equal to the oracle's."""
+    print("case: mixed fused/piecewise", flush=True)
+    from oracle.ssd_oracle import Oracle
+    from paper_2012_05396_amd import binding as B
+    numel, K, k, W = ODD, 3, 2, 2
+    m = Model(numel, K, seed=31)
+    ctx = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, chunk_elems=1024,
+                                  stream=torch.cuda.current_stream().cuda_stream), m.weights)
+    o = Oracle(m.w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=1e-4, mode="f32")
+    pattern = "FFFPFPPFFPFPFFPP"          # F: ssd_step, P: piecewise; first W are warm-up
+    for it, how in enumerate(pattern):
+        p = it % 3
+        d = it - W
+        if how == "F" or it < W:
+            ctx.ssd_step(m.g_dev[p])
+        else:
+            ctx.ssd_server_aggregate_update(m.g_dev[p])
+            for i in range(K):
+                ctx.ssd_worker_glu_update(i, m.g_dev[p][i])
+            if d % k == k - 1:
+                for i in range(K):
+                    ctx.ssd_worker_pull(i)
+        o.step(m.g_host[p])
+        if it >= W and how == "P":
+            # piecewise iterations do not advance ssd_step's iteration counter;
+            # the schedule is keyed on the local update count, which they do
+            pass
+        compare_state(ctx, m, o, exact=True, where="mixed it=%d %s" % (it, how))
+    ctx.close()

@@ -1,0 +1,172 @@
+"""Host-side logic of the HIP library, without a GPU: the library loads and
+exports every symbol the header declares, the schedule function follows
+Algorithm 1 / Algorithm 2, the chunk planner covers every element once, and
+argument checking rejects bad input before anything touches a device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2012_05396_amd import binding as B
+from paper_2012_05396_amd import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "ssd.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(ssd_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"ssd_init", "ssd_server_aggregate_update", "ssd_worker_glu_update", "ssd_step"} <= set(names)
+    lib = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), "libssd.so does not export %s" % n
+
+
+def test_binding_names_match_header():
+    for n in declared_functions():
+        assert hasattr(B.lib, n)
+        if n in ("ssd_init", "ssd_destroy", "ssd_last_error"):
+            continue   # owned by Context / error handling
+        assert hasattr(B, n) or hasattr(B.Context, n), n
+
+
+# ---- schedule (Alg. 1 warm-up loop / steps-delay loop, Alg. 2 pre_weight) ----
+@pytest.mark.parametrize("wp,k", [(0, 1), (1, 2), (3, 4), (5, 3), (9, 5), (7, 8)])
+def test_step_kind_follows_algorithm_1_when_aligned(wp, k):
+    assert (1 + wp) % k == 0
+    W = wp + 1
+    d = 0
+    for num in range(W + 5 * k):
+        kind, pre = B.ssd_step_kind_of(num, W, k, d)
+        if num < wp:
+            assert (kind, pre) == (B.SSD_STEP_WARMUP, B.SSD_PRE_KEEP)
+        elif num == wp:
+            assert (kind, pre) == (B.SSD_STEP_WARMUP_LAST, B.SSD_PRE_KEEP)
+        else:
+            # Alg. 1: Pull when num % k == k-1;  Alg. 2 with loc_update = d
+            assert kind == (B.SSD_STEP_DELAY_PULL if num % k == k - 1 else B.SSD_STEP_DELAY)
+            exp = B.SSD_PRE_INIT if d == 0 else (B.SSD_PRE_REFRESH if d % k == 0 else B.SSD_PRE_KEEP)
+            assert pre == exp
+            d += 1
+
+
+def test_step_kind_matches_oracle_for_unaligned_warmup():
+    import numpy as np
+    from oracle.ssd_oracle import Oracle
+    for W, k in [(2, 4), (0, 3), (5, 2), (1, 1), (3, 0)]:
+        o = Oracle(np.zeros(1, np.float32), K=1, k=k, W=W, lr=0.1, m=0.9, wd=0.0)
+        g = [np.zeros(1, np.float32)]
+        for it in range(W + 3 * max(k, 1) + 1):
+            kind, _ = B.ssd_step_kind_of(it, W, k, o.d)
+            assert kind == o.step(g)
+
+
+def test_step_kind_rejects_negative():
+    with pytest.raises(B.SsdError):
+        B.ssd_step_kind_of(-1, 0, 0, 0)
+
+
+# ---- chunk planner -----------------------------------------------------------
+@pytest.mark.parametrize("chunk", [0, 1024, 2048, 8192])
+@pytest.mark.parametrize("name", ["resnet20", "resnet56", "vgg16"])
+def test_chunks_cover_every_element_once(name, chunk):
+    numel = workloads.numels(workloads.workload(name).tensors)
+    chunks, used = B.ssd_plan_chunks(numel, chunk)
+    assert used % 1024 == 0 and used > 0 and (chunk == 0 or used == chunk)
+    pos = [0] * len(numel)
+    for t, off, ln in chunks:          # in order, contiguous, within bounds
+        assert off == pos[t] and off % used == 0 and 0 < ln <= used
+        pos[t] += ln
+    assert pos == numel
+    assert len(chunks) == sum(-(-n // used) for n in numel)
+
+
+def test_chunk_planner_edge_cases():
+    assert B.ssd_plan_chunks([1], 1024) == ([(0, 0, 1)], 1024)
+    ch, _ = B.ssd_plan_chunks([1024, 1025], 1024)
+    assert ch == [(0, 0, 1024), (1, 0, 1024), (1, 1024, 1)]
+    for bad in ([0], [5, -1]):
+        with pytest.raises(B.SsdError):
+            B.ssd_plan_chunks(bad, 1024)
+    with pytest.raises(B.SsdError):
+        B.ssd_plan_chunks([10], 1000)      # not a multiple of 1024
+
+
+# ---- argument validation (before any device work) ------------------------------
+def _cfg(**kw):
+    d = dict(numel=[100, 5], K=2, k=2, W=1, lr=0.1, momentum=0.9, wd=1e-4)
+    d.update(kw)
+    return B.make_config(**d)
+
+
+@pytest.mark.parametrize("kw", [dict(K=0), dict(K=17), dict(k=-1), dict(W=-1), dict(numel=[3, 0]),
+                                dict(lr=0.0), dict(chunk_elems=100), dict(device=-1)])
+def test_workspace_bytes_rejects_bad_config(kw):
+    with pytest.raises(B.SsdError) as e:
+        B.ssd_workspace_bytes(_cfg(**kw))
+    assert e.value.code == B.SSD_EINVAL and len(str(e.value)) > 20
+
+
+def test_workspace_bytes_counts_the_state_arrays():
+    # k = 0: momentum only.  k > 0: momentum, two pre_weight arrays, K local
+    # weights, K w_loc; each array padded per tensor to 64 elements.
+    a = B.ssd_workspace_bytes(_cfg(k=0))
+    b = B.ssd_workspace_bytes(_cfg(k=2))
+    arr = (128 + 64) * 4
+    assert b - a == (2 + 2 * 2) * arr
+
+
+def test_init_rejects_bad_arguments_without_a_gpu():
+    cfg = _cfg()
+    n = B.ssd_workspace_bytes(cfg)
+    h = C.c_void_p(None)
+    wp = (C.c_void_p * 2)(0x1000, 0x2000)
+    # NULL / misaligned workspace, NULL or misaligned weight pointers, short workspace
+    assert B.lib.ssd_init(C.byref(cfg), wp, None, n, C.byref(h)) == B.SSD_EINVAL
+    assert B.lib.ssd_init(C.byref(cfg), wp, C.c_void_p(0x10010), n, C.byref(h)) == B.SSD_EALIGN
+    assert B.lib.ssd_init(C.byref(cfg), wp, C.c_void_p(0x10000), n - 1, C.byref(h)) == B.SSD_ENOMEM
+    assert b"needed" in B.lib.ssd_last_error(None)
+    bad = (C.c_void_p * 2)(0x1000, 0)
+    assert B.lib.ssd_init(C.byref(cfg), bad, C.c_void_p(0x10000), n, C.byref(h)) == B.SSD_EINVAL
+    bad = (C.c_void_p * 2)(0x1000, 0x2002)
+    assert B.lib.ssd_init(C.byref(cfg), bad, C.c_void_p(0x10000), n, C.byref(h)) == B.SSD_EALIGN
+    assert B.lib.ssd_init(C.byref(cfg), None, C.c_void_p(0x10000), n, C.byref(h)) == B.SSD_EINVAL
+    assert h.value is None
+
+
+def test_null_context_is_rejected():
+    assert B.lib.ssd_step(None, None) == B.SSD_EINVAL
+    assert B.lib.ssd_server_aggregate_update(None, None) == B.SSD_EINVAL
+    assert B.lib.ssd_worker_glu_update(None, 0, None) == B.SSD_EINVAL
+    assert B.lib.ssd_worker_pull(None, 0) == B.SSD_EINVAL
+    assert B.lib.ssd_set_lr(None, 0.1, 0.4) == B.SSD_EINVAL
+    assert B.lib.ssd_get_state(None, None) == B.SSD_EINVAL
+    B.lib.ssd_destroy(None)
+
+
+def test_probe_copy_validates_arguments():
+    assert B.lib.ssd_probe_copy(None, None, 4, None) == B.SSD_EINVAL
+    assert B.lib.ssd_probe_copy(C.c_void_p(0x1000), C.c_void_p(0x2000), 3, None) == B.SSD_EINVAL
+    assert B.lib.ssd_probe_copy(C.c_void_p(0x1004), C.c_void_p(0x2000), 4, None) == B.SSD_EALIGN
+    assert B.lib.ssd_probe_copy(C.c_void_p(0x1000), C.c_void_p(0x2000), 0, None) == B.SSD_OK
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True)
+    assert r.returncode != 0 and "one-GPU" in (r.stderr + r.stdout)
+
+
+def test_workload_shapes_match_the_published_architectures():
+    exp = {"resnet20": (272474, 65), "resnet56": (855770, 173), "resnet50": (25557032, 161),
+           "vgg16": (138357544, 32), "resnet152_k4": (60192808, 467)}
+    for name, (n, t) in exp.items():
+        numel = workloads.numels(workloads.workload(name).tensors)
+        assert (sum(numel), len(numel)) == (n, t)
