@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="vgg16")
     ap.add_argument("--chunk-elems", type=int, default=0)
+    ap.add_argument("--waves-per-cu", type=int, default=0)
+    ap.add_argument("--workers", type=int, default=0, help="override K (not the benchmark configuration)")
+    ap.add_argument("--delay", type=int, default=-1, help="override k (not the benchmark configuration)")
     ap.add_argument("--pool", type=int, default=2, help="distinct gradient sets cycled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
@@ -73,6 +76,10 @@ def main():
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
     wl = workloads.workload(args.workload)
+    if args.workers > 0:
+        wl = wl._replace(K=args.workers, name=wl.name + "[K=%d]" % args.workers)
+    if args.delay >= 0:
+        wl = wl._replace(k=args.delay, name=wl.name + "[k=%d]" % args.delay)
     numel = workloads.numels(wl.tensors)
     N, T, K, k, W = sum(numel), len(numel), wl.K, wl.k, wl.W
 
@@ -85,7 +92,8 @@ def main():
 
     stream = torch.cuda.current_stream()
     cfg = B.make_config(numel, K, k, W, wl.lr, wl.momentum, wl.wd, device=0,
-                        stream=stream.cuda_stream, chunk_elems=args.chunk_elems)
+                        stream=stream.cuda_stream, chunk_elems=args.chunk_elems,
+                        waves_per_cu=args.waves_per_cu)
     ctx = B.Context(cfg, weights)
     view = ctx.ssd_get_state()
 
@@ -181,6 +189,7 @@ def main():
         "config": {"workload": "%s-shaped fp32 parameter set, N=%d elements in T=%d tensors, "
                                "K=%d workers, delay k=%d, SSGD warm-up W=%d" % (wl.name, N, T, K, k, W),
                    "chunk_elems": view.chunk_elems, "num_chunks": view.num_chunks,
+                   "waves_per_cu": args.waves_per_cu or "library default",
                    "gradient_sets_cycled": P, "lr": wl.lr, "momentum": wl.momentum, "wd": wl.wd},
         "bytes_per_elem_cycle_average": {"explicit_arrays_model": round(model_bytes / N, 2),
                                          "moved": round(moved_bytes / N, 2)},

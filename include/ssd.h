@@ -89,7 +89,11 @@ typedef struct {
     int32_t device;        /* HIP device ordinal                              */
     void *stream;          /* hipStream_t; NULL = the default stream          */
     int32_t chunk_elems;   /* elements per work chunk of the multi-tensor
-                              launch; 0 = choose; else a multiple of 1024     */
+                              launch; 0 = choose (256: one 64-lane wave x 4
+                              floats); else a multiple of 256                 */
+    int32_t waves_per_cu;  /* cap on wavefronts resident per compute unit in
+                              the fused launch; 0 = the library's measured
+                              choice per kernel                               */
 } ssd_config;
 
 /* Device-side state, for inspection.  All arrays are "arena" arrays of
@@ -213,7 +217,7 @@ typedef struct {
 } ssd_chunk;
 
 /* Split T tensors into chunks of at most chunk_elems elements (chunk_elems a
- * positive multiple of 1024; 0 = the library's choice for this model).  Every
+ * positive multiple of 256; 0 = the library's choice).  Every
  * element of every tensor lies in exactly one chunk; chunks of a tensor start
  * at multiples of chunk_elems.  Writes up to `capacity` chunks to `out` (may
  * be NULL to count only) and the total number to *count; *chunk_elems_used

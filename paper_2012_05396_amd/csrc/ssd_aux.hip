@@ -107,12 +107,12 @@ hipError_t ssd_launch_pull(int init, unsigned nchunks, hipStream_t s, const ssd_
 }
 
 // n is a multiple of 4 and p is 16-byte aligned (state arrays are padded).
-__global__ __launch_bounds__(SSD_BLOCK) void ssd_fill_zero_kernel(float *p, int64_t n4)
+__global__ __launch_bounds__(SSD_COPY_BLOCK) void ssd_fill_zero_kernel(float *p, int64_t n4)
 {
     typedef float v4 __attribute__((ext_vector_type(4)));
     const v4 z = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t i = (int64_t)blockIdx.x * SSD_BLOCK + threadIdx.x; i < n4;
-         i += (int64_t)gridDim.x * SSD_BLOCK)
+    for (int64_t i = (int64_t)blockIdx.x * SSD_COPY_BLOCK + threadIdx.x; i < n4;
+         i += (int64_t)gridDim.x * SSD_COPY_BLOCK)
         reinterpret_cast<v4 *>(p)[i] = z;
 }
 
@@ -120,18 +120,18 @@ hipError_t ssd_launch_fill_zero(float *p, int64_t n, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
     const int64_t n4 = n / 4;
-    int64_t blocks = (n4 + SSD_BLOCK - 1) / SSD_BLOCK;
+    int64_t blocks = (n4 + SSD_COPY_BLOCK - 1) / SSD_COPY_BLOCK;
     if (blocks > 8192) blocks = 8192;
-    ssd_fill_zero_kernel<<<dim3((unsigned)blocks), dim3(SSD_BLOCK), 0, s>>>(p, n4);
+    ssd_fill_zero_kernel<<<dim3((unsigned)blocks), dim3(SSD_COPY_BLOCK), 0, s>>>(p, n4);
     return hipGetLastError();
 }
 
 // Measurement aid: a plain copy with the library's own load/store helpers.
-__global__ __launch_bounds__(SSD_BLOCK) void ssd_probe_copy_kernel(const float *s, float *d, int64_t n)
+__global__ __launch_bounds__(SSD_COPY_BLOCK) void ssd_probe_copy_kernel(const float *s, float *d, int64_t n)
 {
     cgfloat *src = ssd_global(s);
     gfloat *dst = ssd_global(d);
-    const int64_t e = ((int64_t)blockIdx.x * SSD_BLOCK + threadIdx.x) * 4;
+    const int64_t e = ((int64_t)blockIdx.x * SSD_COPY_BLOCK + threadIdx.x) * 4;
     if (e < n) {
         float x[4];
         ssd_vec<4>::ld(src + e, x);
@@ -144,9 +144,9 @@ extern "C" int ssd_probe_copy(const float *src, float *dst, int64_t n, void *str
     if (!src || !dst || n < 0 || n % 4) return SSD_EINVAL;
     if (!ssd_aligned16_host(src) || !ssd_aligned16_host(dst)) return SSD_EALIGN;
     if (n == 0) return SSD_OK;
-    const int64_t blocks = (n / 4 + SSD_BLOCK - 1) / SSD_BLOCK;
+    const int64_t blocks = (n / 4 + SSD_COPY_BLOCK - 1) / SSD_COPY_BLOCK;
     if (blocks > 0x7fffffffLL) return SSD_EINVAL;
-    ssd_probe_copy_kernel<<<dim3((unsigned)blocks), dim3(SSD_BLOCK), 0, static_cast<hipStream_t>(stream)>>>(
+    ssd_probe_copy_kernel<<<dim3((unsigned)blocks), dim3(SSD_COPY_BLOCK), 0, static_cast<hipStream_t>(stream)>>>(
         src, dst, n);
     return hipGetLastError() == hipSuccess ? SSD_OK : SSD_EHIP;
 }

@@ -16,9 +16,13 @@
 
 #include "../../include/ssd.h"
 
+// Workgroups are single wavefronts: the unit of scheduling is then one wave
+// working on one 256-element (1 KiB per array) tile, and the number of waves
+// resident per compute unit can be capped exactly (see ssd_lds_for_waves).
 #ifndef SSD_BLOCK
-#define SSD_BLOCK 256
+#define SSD_BLOCK 64
 #endif
+#define SSD_COPY_BLOCK 256
 // non-temporal hints on the streaming accesses (build-time switches)
 #ifndef SSD_NT_LOAD
 #define SSD_NT_LOAD 1
@@ -47,6 +51,17 @@ struct ssd_fused_args {
     int64_t A;                // elements per state array (worker stride)
     ssd_hyper h;
 };
+
+// Streaming kernels with dozens of concurrent read and write streams reach
+// their best HBM throughput on MI355X with only a handful of waves per compute
+// unit (few tiles in flight = a narrow window of every array).  The cap is
+// enforced by giving each single-wave workgroup a slice of the 160 KiB LDS
+// that it never touches: waves * slice <= 160 KiB.  0 = no cap.
+static inline unsigned ssd_lds_for_waves(int waves_per_cu)
+{
+    if (waves_per_cu <= 0 || waves_per_cu >= 32) return 0;
+    return (163840u / (unsigned)waves_per_cu) & ~255u;
+}
 
 struct ssd_glu_args {
     const ssd_chunk *chunks;
@@ -157,10 +172,10 @@ static inline bool ssd_aligned16_host(const void *p)
 hipError_t ssd_launch_glu(int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a);
 hipError_t ssd_launch_pull(int init, unsigned nchunks, hipStream_t s, const ssd_pull_args &a);
 hipError_t ssd_launch_fill_zero(float *p, int64_t n, hipStream_t s);
-typedef hipError_t (*ssd_fused_launcher)(int stage, int pre_action, int from_global, unsigned nchunks,
-                                         hipStream_t s, const ssd_fused_args &a);
+typedef hipError_t (*ssd_fused_launcher)(int stage, int pre_action, int from_global, int waves_per_cu,
+                                         unsigned nchunks, hipStream_t s, const ssd_fused_args &a);
 #define SSD_DECL_FUSED(k) \
-    hipError_t ssd_launch_fused_k##k(int, int, int, unsigned, hipStream_t, const ssd_fused_args &);
+    hipError_t ssd_launch_fused_k##k(int, int, int, int, unsigned, hipStream_t, const ssd_fused_args &);
 SSD_DECL_FUSED(1) SSD_DECL_FUSED(2) SSD_DECL_FUSED(3) SSD_DECL_FUSED(4)
 SSD_DECL_FUSED(5) SSD_DECL_FUSED(6) SSD_DECL_FUSED(7) SSD_DECL_FUSED(8)
 SSD_DECL_FUSED(9) SSD_DECL_FUSED(10) SSD_DECL_FUSED(11) SSD_DECL_FUSED(12)

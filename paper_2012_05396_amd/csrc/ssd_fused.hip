@@ -105,13 +105,17 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const ssd_fused_ar
 #define SSD_CAT2(a, b) a##b
 #define SSD_CAT(a, b) SSD_CAT2(a, b)
 
-hipError_t SSD_CAT(ssd_launch_fused_k, SSD_K)(int stage, int pre_action, int from_global, unsigned nchunks,
+hipError_t SSD_CAT(ssd_launch_fused_k, SSD_K)(int stage, int pre_action, int from_global, int waves_per_cu, unsigned nchunks,
                                                hipStream_t s, const ssd_fused_args &a)
 {
     const dim3 grid(nchunks), block(SSD_BLOCK);
+    const unsigned lds = ssd_lds_for_waves(waves_per_cu); // occupancy cap only, never accessed
 #define SSD_GO(ST, PR, FG)                                                         \
     do {                                                                           \
-        ssd_fused_kernel<SSD_K, ST, PR, FG><<<grid, block, 0, s>>>(a);             \
+        if (lds > 65536)                                                           \
+            (void)hipFuncSetAttribute((const void *)ssd_fused_kernel<SSD_K, ST, PR, FG>,   \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        ssd_fused_kernel<SSD_K, ST, PR, FG><<<grid, block, lds, s>>>(a);           \
         return hipGetLastError();                                                  \
     } while (0)
     if (stage == SSD_STAGE_WARMUP) SSD_GO(SSD_STAGE_WARMUP, SSD_PRE_KEEP, false);

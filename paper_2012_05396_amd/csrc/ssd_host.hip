@@ -9,7 +9,6 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -159,8 +158,9 @@ int check_config(const ssd_config *c)
         if (c->numel[t] < 1) return fail_init(SSD_EINVAL, "numel[%d] = %lld, must be >= 1", t, (long long)c->numel[t]);
     if (c->delay_k > 0 && !(c->lr != 0.0f))
         return fail_init(SSD_EINVAL, "lr = 0 with delay_k > 0: grad_sync divides by lr*k");
-    if (c->chunk_elems < 0 || c->chunk_elems % 1024 != 0)
-        return fail_init(SSD_EINVAL, "chunk_elems = %d, must be 0 or a positive multiple of 1024", c->chunk_elems);
+    if (c->chunk_elems < 0 || c->chunk_elems % 256 != 0)
+        return fail_init(SSD_EINVAL, "chunk_elems = %d, must be 0 or a positive multiple of 256", c->chunk_elems);
+    if (c->waves_per_cu < 0) return fail_init(SSD_EINVAL, "waves_per_cu = %d, must be >= 0", c->waves_per_cu);
     if (c->device < 0) return fail_init(SSD_EINVAL, "device = %d", c->device);
     return SSD_OK;
 }
@@ -179,9 +179,7 @@ int make_layout(const ssd_config *c, Layout *L)
     if (rc != SSD_OK) return rc;
     if (L->num_chunks > 0x7fffffffLL) return fail_init(SSD_EINVAL, "model needs %lld chunks, more than one launch holds", (long long)L->num_chunks);
     size_t o = 0;
-    size_t pad = 0;
-    if (const char *e = getenv("SSD_STRIDE_PAD_BYTES")) pad = (size_t)atoll(e);
-    const size_t arr = round_up(sizeof(float) * (size_t)a + pad, kWsAlign);
+    const size_t arr = round_up(sizeof(float) * (size_t)a, kWsAlign);
     L->stride = (int64_t)(arr / sizeof(float));
     L->off_mom = o, o += arr;
     if (c->delay_k > 0) {
@@ -265,18 +263,12 @@ int ssd_plan_chunks(const int64_t *numel, int32_t T, int32_t chunk_elems, ssd_ch
                     int64_t capacity, int64_t *count, int32_t *used)
 {
     if (!numel || T < 1 || !count) return fail_init(SSD_EINVAL, "ssd_plan_chunks: NULL argument or T < 1");
-    if (chunk_elems < 0 || chunk_elems % 1024 != 0)
-        return fail_init(SSD_EINVAL, "chunk_elems = %d, must be 0 or a positive multiple of 1024", chunk_elems);
-    int64_t N = 0;
-    for (int t = 0; t < T; ++t) {
+    if (chunk_elems < 0 || chunk_elems % 256 != 0)
+        return fail_init(SSD_EINVAL, "chunk_elems = %d, must be 0 or a positive multiple of 256", chunk_elems);
+    for (int t = 0; t < T; ++t)
         if (numel[t] < 1) return fail_init(SSD_EINVAL, "numel[%d] = %lld, must be >= 1", t, (long long)numel[t]);
-        N += numel[t];
-    }
-    int64_t c = chunk_elems;
-    if (c == 0) { // enough chunks to fill 256 compute units several times over
-        c = 8192;
-        while (c > 1024 && N / c < 2048) c /= 2;
-    }
+    // one tile of a single-wave workgroup: 64 lanes x 4 floats
+    const int64_t c = chunk_elems == 0 ? 256 : chunk_elems;
     int64_t n = 0;
     for (int t = 0; t < T; ++t)
         for (int64_t off = 0; off < numel[t]; off += c, ++n)
@@ -440,6 +432,16 @@ static int check_grads(ssd_ctx *c, const float *const *const *grads)
     return SSD_OK;
 }
 
+// Resident waves per compute unit that gave the highest HBM throughput when
+// measured on MI355X (sweeps over 3..16 waves; K = 4 and 8 on a 138 M-element
+// model, K = 16 on a 60 M-element one).  The optimum is flat within +-1.
+static int default_waves_per_cu(int K, int stage, int from_global)
+{
+    if (stage == SSD_STAGE_WARMUP) return 8;       // K+2 read streams, 2 write streams
+    if (!from_global) return 7;                    // 2K+3 read streams, K+2 write streams
+    return K <= 4 ? 7 : 4;                         // K+3 read streams, K+3 write streams
+}
+
 static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
 {
     static const ssd_fused_launcher table[SSD_MAX_WORKERS] = {
@@ -459,7 +461,9 @@ static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
     a.wl = c->wl;
     a.A = c->stride_elems();
     a.h = c->h;
-    e = table[c->cfg.num_workers - 1](stage, pre_action, from_global, (unsigned)c->L.num_chunks, c->stream, a);
+    const int waves = c->cfg.waves_per_cu > 0 ? c->cfg.waves_per_cu
+                                              : default_waves_per_cu(c->cfg.num_workers, stage, from_global);
+    e = table[c->cfg.num_workers - 1](stage, pre_action, from_global, waves, (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the fused kernel");
     return SSD_OK;
 }

@@ -125,7 +125,7 @@ def compare_state(ctx, model, o, exact=True, tol=1e-5, where=""):
         chk("w_loc[%d]" % i, effective_w_loc(ctx, model, i), o.wloc[i])
 
 
-def run_schedule(numel, K, k, W, steps, hp=None, mode="f32", chunk_elems=1024, seed=0,
+def run_schedule(numel, K, k, W, steps, hp=None, mode="f32", chunk_elems=256, seed=0,
                  w_shift=0, g_shift=0, g_scale=1e-2, check_every=1, P=3, lr_changes=None):
     """Drive ssd_step and the oracle side by side; compare after each step."""
     from paper_2012_05396_amd import binding as B

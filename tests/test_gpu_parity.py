@@ -48,7 +48,7 @@ def test_hyperparameters_and_lr_change():
 
 def test_large_chunks_and_multi_pass():
     print("case: chunk sizes", flush=True)
-    for ce in (1024, 2048, 8192, 0):
+    for ce in (256, 1024, 2048, 8192, 0):
         run_schedule([20000, 8192, 8193, 7], K=4, k=2, W=1, steps=5, chunk_elems=ce, seed=ce)
 
 
@@ -95,8 +95,8 @@ def test_piecewise_calls_equal_fused_step():
     ma = Model(numel, K, seed=77)
     mb = Model(numel, K, seed=77)
     s = torch.cuda.current_stream().cuda_stream
-    ca = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, stream=s, chunk_elems=1024), ma.weights)
-    cb = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, stream=s, chunk_elems=1024), mb.weights)
+    ca = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, stream=s, chunk_elems=256), ma.weights)
+    cb = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, stream=s, chunk_elems=256), mb.weights)
     o = Oracle(ma.w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=1e-4, mode="f32")
     for it in range(W + 3 * k + 2):
         p = it % 3
@@ -165,7 +165,7 @@ def test_materialize_writes_out_recorded_state():
     from paper_2012_05396_amd import binding as B
     numel, K, k, W = ODD, 3, 2, 1
     m = Model(numel, K, seed=21)
-    ctx = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, chunk_elems=1024,
+    ctx = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, chunk_elems=256,
                                   stream=torch.cuda.current_stream().cuda_stream), m.weights)
     o = Oracle(m.w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=1e-4, mode="f32")
     for it in range(W + 3 * k):
@@ -200,7 +200,7 @@ def test_mixed_fused_and_piecewise_iterations():
     from paper_2012_05396_amd import binding as B
     numel, K, k, W = ODD, 3, 2, 2
     m = Model(numel, K, seed=31)
-    ctx = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, chunk_elems=1024,
+    ctx = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, chunk_elems=256,
                                   stream=torch.cuda.current_stream().cuda_stream), m.weights)
     o = Oracle(m.w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=1e-4, mode="f32")
     pattern = "FFFPFPPFFPFPFFPP"          # F: ssd_step, P: piecewise; first W are warm-up

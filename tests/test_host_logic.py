@@ -73,12 +73,12 @@ def test_step_kind_rejects_negative():
 
 
 # ---- chunk planner -----------------------------------------------------------
-@pytest.mark.parametrize("chunk", [0, 1024, 2048, 8192])
+@pytest.mark.parametrize("chunk", [0, 256, 1024, 8192])
 @pytest.mark.parametrize("name", ["resnet20", "resnet56", "vgg16"])
 def test_chunks_cover_every_element_once(name, chunk):
     numel = workloads.numels(workloads.workload(name).tensors)
     chunks, used = B.ssd_plan_chunks(numel, chunk)
-    assert used % 1024 == 0 and used > 0 and (chunk == 0 or used == chunk)
+    assert used % 256 == 0 and used > 0 and (chunk == used or (chunk == 0 and used == 256))
     pos = [0] * len(numel)
     for t, off, ln in chunks:          # in order, contiguous, within bounds
         assert off == pos[t] and off % used == 0 and 0 < ln <= used
@@ -89,13 +89,14 @@ def test_chunks_cover_every_element_once(name, chunk):
 
 def test_chunk_planner_edge_cases():
     assert B.ssd_plan_chunks([1], 1024) == ([(0, 0, 1)], 1024)
+    assert B.ssd_plan_chunks([257], 0) == ([(0, 0, 256), (0, 256, 1)], 256)
     ch, _ = B.ssd_plan_chunks([1024, 1025], 1024)
     assert ch == [(0, 0, 1024), (1, 0, 1024), (1, 1024, 1)]
     for bad in ([0], [5, -1]):
         with pytest.raises(B.SsdError):
             B.ssd_plan_chunks(bad, 1024)
     with pytest.raises(B.SsdError):
-        B.ssd_plan_chunks([10], 1000)      # not a multiple of 1024
+        B.ssd_plan_chunks([10], 1000)      # not a multiple of 256
 
 
 # ---- argument validation (before any device work) ------------------------------
@@ -106,7 +107,8 @@ def _cfg(**kw):
 
 
 @pytest.mark.parametrize("kw", [dict(K=0), dict(K=17), dict(k=-1), dict(W=-1), dict(numel=[3, 0]),
-                                dict(lr=0.0), dict(chunk_elems=100), dict(device=-1)])
+                                dict(lr=0.0), dict(chunk_elems=100), dict(device=-1),
+                                dict(waves_per_cu=-2)])
 def test_workspace_bytes_rejects_bad_config(kw):
     with pytest.raises(B.SsdError) as e:
         B.ssd_workspace_bytes(_cfg(**kw))
