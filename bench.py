@@ -25,7 +25,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE + WRITE_SIZE, scaled by what the same counters read on a copy of
 # known size); see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/ssd_fused_kernel_vgg16_K8_k4.txt: 10,336,185 KiB read + 5,400,758 KiB written
+    "vgg16": 16114629632,
+}
 
 
 def bytes_per_element(K, kind, pre_action, from_global):

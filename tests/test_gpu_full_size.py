@@ -1,0 +1,186 @@
+"""Full-size GPU parity on the five benchmark configurations, in the launch
+configuration bench.py times (library defaults: 256-element chunks, measured
+waves-per-CU caps).
+
+The path is element-wise, so the oracle can compute any element on its own:
+a seeded sample of elements of every tensor (first and last elements, both
+sides of chunk boundaries, random positions) is gathered from the inputs, run
+through the CPU oracle for the whole schedule, and compared bit for bit
+(binary32 oracle) and within 1e-5 (binary64 oracle) with the same elements of
+the GPU state, after each of the last iterations so that every kernel variant
+is covered.  Properties that hold at any size are checked on whole arrays on
+the device: pre_weight equals the global weight as of the last Pull, and the
+fused step equals the piecewise calls on every element.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle.ssd_oracle import Oracle
+from paper_2012_05396_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+SAMPLES_PER_TENSOR = 2048
+
+
+def sample_indices(numel, chunk, rng):
+    """Element indices inside one tensor worth checking."""
+    idx = set(range(min(numel, 8))) | set(range(max(0, numel - 8), numel))
+    nchunks = -(-numel // chunk)
+    for c in rng.choice(nchunks, size=min(nchunks, 6), replace=False):
+        for e in (c * chunk - 1, c * chunk, c * chunk + 1, c * chunk + 3, c * chunk + 4,
+                  c * chunk + chunk - 1):
+            if 0 <= e < numel:
+                idx.add(int(e))
+    if numel > len(idx):
+        idx |= set(int(x) for x in rng.integers(0, numel, size=min(SAMPLES_PER_TENSOR, numel)))
+    return np.array(sorted(idx), np.int64)
+
+
+def bit_equal(a, b):
+    a, b = np.asarray(a, np.float32), np.asarray(b, np.float32)
+    return np.array_equal(a.view(np.int32), b.view(np.int32))
+
+
+def run_full(name, piecewise_check=False):
+    from paper_2012_05396_amd import binding as B
+    wl = workloads.workload(name)
+    dev = torch.device("cuda", 0)
+    numel = workloads.numels(wl.tensors)
+    T, K, k, W = len(numel), wl.K, wl.k, wl.W
+    steps = W + wl.steps
+    print("case: %s N=%d T=%d K=%d k=%d steps=%d" % (name, sum(numel), T, K, k, steps), flush=True)
+    rng = np.random.default_rng(wl.seed)
+
+    wflat, offs = workloads.initial_weights(wl, device=dev)
+    weights = workloads.views(wflat, wl.tensors, offs)
+    P = 2
+    gsets = [workloads.gradient_set(wl, p, device=dev) for p in range(P)]
+    gviews = [[workloads.views(g, wl.tensors, offs) for g in gs] for gs in gsets]
+    tables = [B.GradTable(g) for g in gviews]
+    stream = torch.cuda.current_stream().cuda_stream
+    mk = lambda: B.make_config(numel, K, k, W, wl.lr, wl.momentum, wl.wd, stream=stream)
+    ctx = B.Context(mk(), weights)
+    v = ctx.ssd_get_state()
+    assert v.chunk_elems == 256
+
+    # sample: indices into the caller's flat buffers and into the arena
+    flat_idx, arena_idx = [], []
+    for t in range(T):
+        idx = sample_indices(numel[t], v.chunk_elems, rng)
+        flat_idx.append(idx + offs[t])
+        arena_idx.append(idx + v.tensor_offset[t])
+    flat_idx = torch.from_numpy(np.concatenate(flat_idx)).to(dev)
+    arena_idx = torch.from_numpy(np.concatenate(arena_idx)).to(dev)
+    S = flat_idx.numel()
+    take = lambda flat, idx: flat.index_select(0, idx).cpu().numpy()
+    w0 = take(wflat, flat_idx)
+    gh = [[take(g, flat_idx) for g in gs] for gs in gsets]
+    oracles = [Oracle(w0, K=K, k=k, W=W, lr=wl.lr, m=wl.momentum, wd=wl.wd, mode=m)
+               for m in ("f32", "f64")]
+
+    ctx2 = None
+    if piecewise_check:
+        w2 = wflat.clone()
+        ctx2 = B.Context(mk(), workloads.views(w2, wl.tensors, offs))
+
+    def arena(which, worker=0):
+        vv = ctx.ssd_get_state()
+        ptr = getattr(vv, which)
+        count = K if which in ("w_local", "w_loc") else 1
+        a, _ = ctx._arena(ptr, count)
+        return a[worker]
+
+    def check(it):
+        """Compare the sample with both oracles, and whole-array properties."""
+        # ---- compare the sample with both oracles ----
+        torch.cuda.synchronize()
+        vv = ctx.ssd_get_state()
+        o32, o64 = oracles
+        got = {"w": take(wflat, flat_idx), "mom": take(arena("mom"), arena_idx)}
+        exp32 = {"w": o32.w, "mom": o32.mom}
+        exp64 = {"w": o64.w, "mom": o64.mom}
+        if k > 0 and vv.has_local:
+            for i in range(K):
+                wl_i = got["w"] if vv.w_local_is_global else take(arena("w_local", i), arena_idx)
+                got["w_local%d" % i] = wl_i
+                exp32["w_local%d" % i], exp64["w_local%d" % i] = o32.wl[i], o64.wl[i]
+                if vv.w_loc_where == B.SSD_W_LOC_IS_GLOBAL:
+                    wloc_i = got["w"]
+                elif vv.w_loc_where == B.SSD_W_LOC_IN_W_LOCAL:
+                    wloc_i = take(arena("w_local", i), arena_idx)
+                else:
+                    wloc_i = take(arena("w_loc", i), arena_idx)
+                got["w_loc%d" % i] = wloc_i
+                exp32["w_loc%d" % i], exp64["w_loc%d" % i] = o32.wloc[i], o64.wloc[i]
+            if o32.d > 0:
+                got["pre"] = take(arena("pre"), arena_idx)
+                exp32["pre"], exp64["pre"] = o32.pre[0], o64.pre[0]
+        for name_, g in got.items():
+            assert bit_equal(g, exp32[name_]), "%s it=%d %s: sampled elements differ from the binary32 oracle" % (
+                name, it, name_)
+            e = exp64[name_]
+            err = np.max(np.abs(g.astype(np.float64) - e)) / max(np.max(np.abs(e)), 1e-30)
+            assert err <= 1e-5, "%s it=%d %s: rel err %.3e vs binary64 oracle" % (name, it, name_, err)
+        # ---- whole-array properties, on the device ----
+        if k > 0 and o32.d > 0 and (o32.d - 1) % k == 0 and o32.d > 1 and last_pull_w is not None:
+            # pre_weight was just refreshed: it is the global weight of the previous Pull
+            pre = arena("pre")
+            for t in range(T):
+                a = pre[vv.tensor_offset[t]:vv.tensor_offset[t] + numel[t]]
+                b = last_pull_w[offs[t]:offs[t] + numel[t]]
+                assert torch.equal(a.view(torch.int32), b.view(torch.int32)), (name, it, t)
+
+    last_pull_w = None      # global weight as of the last Pull / hand-over
+    for it in range(steps):
+        p = it % P
+        ctx.ssd_step(tables[p])
+        kinds = [o.step(gh[p]) for o in oracles]
+        if ctx2 is not None:
+            ctx2.ssd_server_aggregate_update(tables[p])
+            if kinds[0] == 1:
+                for i in range(K):
+                    ctx2.ssd_worker_pull(i)
+            elif kinds[0] >= 2:
+                for i in range(K):
+                    ctx2.ssd_worker_glu_update(i, gviews[p][i])
+                if kinds[0] == 3:
+                    for i in range(K):
+                        ctx2.ssd_worker_pull(i)
+        if it >= steps - (k + 2) or it == W:
+            check(it)
+        if kinds[0] in (1, 3):
+            last_pull_w = wflat.clone()
+    if ctx2 is not None:
+        # the fused step equals the piecewise calls on every element
+        ctx.ssd_materialize()
+        torch.cuda.synchronize()
+        assert torch.equal(wflat.view(torch.int32), w2.view(torch.int32))
+        va, vb = ctx.ssd_get_state(), ctx2.ssd_get_state()
+        for which, cnt in (("mom", 1), ("pre", 1), ("w_local", K)):
+            if k == 0 and which != "mom":
+                continue
+            a, _ = ctx._arena(getattr(va, which), cnt)
+            b, _ = ctx2._arena(getattr(vb, which), cnt)
+            for t in range(T):
+                sl = slice(va.tensor_offset[t], va.tensor_offset[t] + numel[t])
+                assert torch.equal(a[:, sl].view(torch.int32), b[:, sl].view(torch.int32)), (name, which, t)
+    ctx.close()
+    if ctx2 is not None:
+        ctx2.close()
+    del gsets, gviews, tables, wflat
+    torch.cuda.empty_cache()
+    return S
+
+
+
+@pytest.mark.parametrize("name", ["resnet20", "resnet56", "resnet50", "vgg16", "resnet152_k2",
+                                  "resnet152_k4", "resnet152_k8"])
+def test_full_size_sampled_parity(name):
+    run_full(name)
+
+
+@pytest.mark.parametrize("name", ["resnet56", "resnet50"])
+def test_full_size_fused_equals_piecewise_everywhere(name):
+    run_full(name, piecewise_check=True)
