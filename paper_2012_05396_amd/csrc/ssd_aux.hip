@@ -25,16 +25,15 @@ __device__ __forceinline__ void ssd_glu_elems(const ssd_hyper &h, cgfloat *gp, g
 template <int PRE>
 __global__ __launch_bounds__(SSD_BLOCK) void ssd_glu_kernel(const ssd_glu_args a)
 {
-    const ssd_chunk c = a.chunks[blockIdx.x];
-    const ssd_tensor_desc td = a.tensors[c.tensor];
-    const float *g = a.gptr[c.tensor];
+    ssd_tensor_desc td;
+    const ssd_block blk = ssd_locate(a.tab, blockIdx.x, td);
+    const float *g = a.gptr[blk.tensor];
     const bool vec = ssd_aligned16(g);
-    cgfloat *gp = ssd_global(g) + c.offset;
-    const int64_t ao = td.arena_off + c.offset;
-    gfloat *wlp = ssd_global(a.wl) + ao;
-    cgfloat *presrc = ssd_global(a.pre_src) + ao;
-    gfloat *predst = ssd_global(a.pre_dst) + ao;
-    const unsigned len = (unsigned)c.len, tid = threadIdx.x;
+    cgfloat *gp = ssd_global(g) + blk.off;
+    gfloat *wlp = ssd_global(a.wl) + blk.ao;
+    cgfloat *presrc = ssd_global(a.pre_src) + blk.ao;
+    gfloat *predst = ssd_global(a.pre_dst) + blk.ao;
+    const unsigned len = blk.len, tid = threadIdx.x;
     if (vec) {
         const unsigned len4 = len & ~3u;
         for (unsigned e = tid * 4; e < len4; e += SSD_BLOCK * 4)
@@ -78,13 +77,12 @@ __device__ __forceinline__ void ssd_pull_elems(cgfloat *wp, gfloat *wlp, gfloat 
 template <bool INIT>
 __global__ __launch_bounds__(SSD_BLOCK) void ssd_pull_kernel(const ssd_pull_args a)
 {
-    const ssd_chunk c = a.chunks[blockIdx.x];
-    const ssd_tensor_desc td = a.tensors[c.tensor];
+    ssd_tensor_desc td;
+    const ssd_block blk = ssd_locate(a.tab, blockIdx.x, td);
     const bool vec = ssd_aligned16(td.w);
-    cgfloat *wp = ssd_global((const float *)td.w) + c.offset;
-    const int64_t ao = td.arena_off + c.offset;
-    gfloat *wlp = ssd_global(a.wl) + ao, *wlocp = ssd_global(a.wloc) + ao;
-    const unsigned len = (unsigned)c.len, tid = threadIdx.x;
+    cgfloat *wp = ssd_global((const float *)td.w) + blk.off;
+    gfloat *wlp = ssd_global(a.wl) + blk.ao, *wlocp = ssd_global(a.wloc) + blk.ao;
+    const unsigned len = blk.len, tid = threadIdx.x;
     if (vec) {
         const unsigned len4 = len & ~3u;
         for (unsigned e = tid * 4; e < len4; e += SSD_BLOCK * 4)

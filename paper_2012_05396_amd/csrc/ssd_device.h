@@ -30,12 +30,41 @@
 #ifndef SSD_NT_STORE
 #define SSD_NT_STORE 1
 #endif
+// 128-bit stores are emitted as "global_store_dwordx4 ... sc1 nt" (agent scope
+// + non-temporal), which the compiler has no builtin for; measured 1-2 %
+// faster than plain "nt" on MI355X.  The compiler cannot see into the asm, so
+// the wait states the ISA requires between a store of more than 64 bits and a
+// VALU write of its data registers are supplied by the s_nop that follows it.
+// SSD_STORE_ASM=0 falls back to __builtin_nontemporal_store.
+#ifndef SSD_STORE_ASM
+#define SSD_STORE_ASM 1
+#endif
 
 enum { SSD_STAGE_WARMUP = 0, SSD_STAGE_DELAY = 2 };
 
+// Work decomposition.  The state arrays are "arena" arrays cut into blocks of
+// C = chunk_elems elements; tensor t owns the blocks first_block[t] ..
+// first_block[t+1]-1 (its last block is padded), so block b of the launch is
+// arena elements [b*C, b*C + C) of every state array -- known from blockIdx
+// alone -- and elements [(b - first_block[t])*C, ...) of tensor t of the
+// caller's arrays, for which one 4-byte table entry names t.
 struct ssd_tensor_desc {
-    float *w;          // global weight of this tensor (caller-owned)
-    int64_t arena_off; // element offset of the tensor inside every state array
+    float *w;            // global weight of this tensor (caller-owned)
+    int64_t first_block; // first arena block of the tensor
+    int64_t numel;
+};
+
+struct ssd_tables {
+    const int32_t *block_tensor;     // [num_blocks]
+    const ssd_tensor_desc *tensors;  // [T]
+    unsigned C;                      // elements per block
+};
+
+struct ssd_block {
+    int tensor;
+    unsigned len;  // valid elements of this block, 1..C
+    int64_t off;   // element offset inside the tensor
+    int64_t ao;    // element offset inside every state array
 };
 
 struct ssd_hyper {
@@ -44,9 +73,11 @@ struct ssd_hyper {
 };
 
 struct ssd_fused_args {
-    const ssd_chunk *chunks;
-    const ssd_tensor_desc *tensors;
-    const float *const *gptr; // [T][K] gradient pointers, worker index fastest
+    ssd_tables tab;
+    // [T][K+3] 8-byte words per tensor: weight pointer, first_block, numel,
+    // then the K gradient pointers -- everything a wave needs about the
+    // caller's arrays in one contiguous record
+    const int64_t *rec;
     float *mom, *pre, *wl;
     int64_t A;                // elements per state array (worker stride)
     ssd_hyper h;
@@ -64,8 +95,7 @@ static inline unsigned ssd_lds_for_waves(int waves_per_cu)
 }
 
 struct ssd_glu_args {
-    const ssd_chunk *chunks;
-    const ssd_tensor_desc *tensors;
+    ssd_tables tab;
     const float *const *gptr; // [T] gradient pointers of the one worker
     const float *pre_src;     // pre_weight array to read
     float *pre_dst;           // pre_weight array to write (init / refresh)
@@ -74,10 +104,22 @@ struct ssd_glu_args {
 };
 
 struct ssd_pull_args {
-    const ssd_chunk *chunks;
-    const ssd_tensor_desc *tensors;
+    ssd_tables tab;
     float *wl, *wloc;         // this worker's arrays
 };
+
+static __device__ __forceinline__ ssd_block ssd_locate(const ssd_tables &tab, unsigned b,
+                                                       ssd_tensor_desc &td)
+{
+    ssd_block k;
+    k.tensor = tab.block_tensor[b];
+    td = tab.tensors[k.tensor];
+    k.off = ((int64_t)b - td.first_block) * tab.C;
+    const int64_t left = td.numel - k.off;
+    k.len = left < (int64_t)tab.C ? (unsigned)left : tab.C;
+    k.ao = (int64_t)b * tab.C;
+    return k;
+}
 
 __device__ __forceinline__ void ssd_server_elem(float S, float w, float mom, const ssd_hyper &h,
                                                 float &w_new, float &mom_new)
@@ -150,7 +192,11 @@ template <> struct ssd_vec<4> {
     static __device__ __forceinline__ void st(gfloat *p, const float (&x)[4])
     {
         v4 v = {x[0], x[1], x[2], x[3]};
-#if SSD_NT_STORE
+#if SSD_STORE_ASM == 1
+        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+#elif SSD_STORE_ASM == 2
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+#elif SSD_NT_STORE
         __builtin_nontemporal_store(v, (gv4 *)p);
 #else
         *(gv4 *)p = v;

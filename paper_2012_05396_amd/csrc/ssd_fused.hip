@@ -1,17 +1,23 @@
 // Fused multi-tensor kernel of one SSD-SGD iteration, for K = SSD_K workers.
 //
-// One workgroup takes one entry of the chunk table (a run of at most
-// chunk_elems elements of one layer tensor) and, per element, reads the K
-// gradients, the global weight and the momentum exactly once, applies the
-// server update (Eq. (server), momentum rule of Sec. 3.2.1) and -- in the
-// steps-delay stage -- the K GLU updates of Algorithm 2 (Eq. (glu-update),
-// grad_sync of Sec. 3.3) on the K local weights.  What Algorithm 1 does at the
-// end of an iteration moves no data here: after the hand-over at the end of
-// warm-up and after a Pull, every w'_i equals the global weight, so the host
-// only records that fact and the next launch (template flag FG) takes w'_i from
-// the global weight it loads anyway.  All K gradient loads and all K local-weight loads of a
-// thread are issued before the first use, as 128-bit accesses whenever every
-// pointer of the tensor is 16-byte aligned.
+// One single-wave workgroup takes one block of the arena (chunk_elems elements
+// of one layer tensor) and, per element, reads the K gradients, the global
+// weight, the momentum, pre_weight and the K local weights exactly once,
+// applies the server update (Eq. (server), momentum rule of Sec. 3.2.1) and
+// -- in the steps-delay stage -- the K GLU updates of Algorithm 2
+// (Eq. (glu-update), grad_sync of Sec. 3.3) on the K local weights.  What
+// Algorithm 1 does at the end of an iteration moves no data here: after the
+// hand-over at the end of warm-up and after a Pull, every w'_i equals the
+// global weight, so the host only records that fact and the next launch
+// (template flag FG) takes w'_i from the global weight it loads anyway.
+//
+// Order of issue inside a wave: the loads of the library's own state (momentum,
+// pre_weight, K local weights) need nothing but blockIdx, so they go out first;
+// the two table lookups that lead to the caller's pointers (block -> tensor,
+// tensor -> one record with the weight and K gradient pointers) overlap with
+// them; then the gradient and
+// weight loads; then arithmetic and stores.  128-bit accesses whenever every
+// caller pointer of the tensor is 16-byte aligned, else element by element.
 //
 // Compiled once per K (-DSSD_K=1..16) so that the worker loops unroll.
 #include "ssd_device.h"
@@ -20,24 +26,35 @@
 #error "compile with -DSSD_K=<number of workers>"
 #endif
 
+template <int K, int VW> struct ssd_state_regs {
+    float mo[VW], p[VW], wl[K][VW];
+};
+
 template <int K, int STAGE, int PRE, bool FG, int VW>
-__device__ __forceinline__ void ssd_fused_elems(const ssd_fused_args &a, cgfloat *const (&gp)[K],
-                                                gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp,
-                                                unsigned e)
+__device__ __forceinline__ void ssd_load_state(const ssd_fused_args &a, gfloat *momp, gfloat *prep,
+                                               gfloat *wlp, unsigned e, ssd_state_regs<K, VW> &s)
 {
     typedef ssd_vec<VW> V;
-    float g[K][VW], w[VW], mo[VW], wl[K][VW], p[VW];
+    V::ld(momp + e, s.mo);
+    if (STAGE == SSD_STAGE_DELAY) {
+        if (PRE != SSD_PRE_INIT) V::ld(prep + e, s.p);
+        if (!FG) {
+#pragma unroll
+            for (int i = 0; i < K; ++i) V::ld(wlp + i * a.A + e, s.wl[i]);
+        }
+    }
+}
+
+template <int K, int STAGE, int PRE, bool FG, int VW>
+__device__ __forceinline__ void ssd_finish(const ssd_fused_args &a, cgfloat *const (&gp)[K], gfloat *wp,
+                                           gfloat *momp, gfloat *prep, gfloat *wlp, unsigned e,
+                                           const ssd_state_regs<K, VW> &s)
+{
+    typedef ssd_vec<VW> V;
+    float g[K][VW], w[VW];
 #pragma unroll
     for (int i = 0; i < K; ++i) V::ld(gp[i] + e, g[i]);
     V::ld(wp + e, w);
-    V::ld(momp + e, mo);
-    if (STAGE == SSD_STAGE_DELAY) {
-        if (!FG) {
-#pragma unroll
-            for (int i = 0; i < K; ++i) V::ld(wlp + i * a.A + e, wl[i]);
-        }
-        if (PRE != SSD_PRE_INIT) V::ld(prep + e, p);
-    }
 
     float wn[VW], mn[VW];
 #pragma unroll
@@ -45,7 +62,7 @@ __device__ __forceinline__ void ssd_fused_elems(const ssd_fused_args &a, cgfloat
         float S = g[0][v];
 #pragma unroll
         for (int i = 1; i < K; ++i) S = S + g[i][v];
-        ssd_server_elem(S, w[v], mo[v], a.h, wn[v], mn[v]);
+        ssd_server_elem(S, w[v], s.mo[v], a.h, wn[v], mn[v]);
     }
     V::st(momp + e, mn);
     V::st(wp + e, wn);
@@ -55,14 +72,14 @@ __device__ __forceinline__ void ssd_fused_elems(const ssd_fused_args &a, cgfloat
         // iteration's server update (after a Pull, or at the end of warm-up),
         // which is in registers already; the w' arrays are not read.
         // Alg. 2: pre_weight takes w' as it was before this update.
-        if (PRE != SSD_PRE_KEEP) V::st(prep + e, FG ? w : wl[0]);
+        if (PRE != SSD_PRE_KEEP) V::st(prep + e, FG ? w : s.wl[0]);
 #pragma unroll
         for (int i = 0; i < K; ++i) {
             float r[VW];
 #pragma unroll
             for (int v = 0; v < VW; ++v) {
-                const float wli = FG ? w[v] : wl[i][v];
-                const float pv = (PRE == SSD_PRE_INIT) ? wli : p[v];
+                const float wli = FG ? w[v] : s.wl[i][v];
+                const float pv = (PRE == SSD_PRE_INIT) ? wli : s.p[v];
                 r[v] = ssd_glu_elem(g[i][v], wli, pv, a.h);
             }
             V::st(wlp + i * a.A + e, r);
@@ -70,35 +87,67 @@ __device__ __forceinline__ void ssd_fused_elems(const ssd_fused_args &a, cgfloat
     }
 }
 
+// One 256-element tile: lane l owns elements e0 .. e0+3 (e0 = base + 4l).
+// Full vectors take the 128-bit path; a lane at the ragged end of the block,
+// or any lane when a caller pointer is not 16-byte aligned, goes element by
+// element -- in both cases with the state values preloaded in `s`.
+template <int K, int STAGE, int PRE, bool FG>
+__device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, cgfloat *const (&gp)[K], gfloat *wp,
+                                         gfloat *momp, gfloat *prep, gfloat *wlp, unsigned e0,
+                                         unsigned len, bool vec, const ssd_state_regs<K, 4> &s)
+{
+    if (vec && e0 + 3 < len) {
+        ssd_finish<K, STAGE, PRE, FG, 4>(a, gp, wp, momp, prep, wlp, e0, s);
+    } else if (e0 < len) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if (e0 + v < len) {
+                ssd_state_regs<K, 1> s1;
+                s1.mo[0] = s.mo[v];
+                s1.p[0] = s.p[v];
+#pragma unroll
+                for (int i = 0; i < K; ++i) s1.wl[i][0] = s.wl[i][v];
+                ssd_finish<K, STAGE, PRE, FG, 1>(a, gp, wp, momp, prep, wlp, e0 + v, s1);
+            }
+        }
+    }
+}
+
 template <int K, int STAGE, int PRE, bool FG>
 __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const ssd_fused_args a)
 {
-    const ssd_chunk c = a.chunks[blockIdx.x];
-    const ssd_tensor_desc td = a.tensors[c.tensor];
-    cgfloat *gp[K];
-    bool vec = ssd_aligned16(td.w);
-#pragma unroll
-    for (int i = 0; i < K; ++i) {
-        const float *g = a.gptr[(int64_t)c.tensor * K + i];
-        vec = vec && ssd_aligned16(g);
-        gp[i] = ssd_global(g) + c.offset;
-    }
-    gfloat *wp = ssd_global(td.w) + c.offset;
-    const int64_t ao = td.arena_off + c.offset;
+    const unsigned lane = threadIdx.x;
+    const int t = a.tab.block_tensor[blockIdx.x]; // head of the lookup chain: request it first
+    // state arrays: addressed by blockIdx alone, always 16-byte aligned, and
+    // padded to whole blocks, so the first tile is requested right away
+    const int64_t ao = (int64_t)blockIdx.x * a.tab.C;
     gfloat *momp = ssd_global(a.mom) + ao, *prep = ssd_global(a.pre) + ao;
     gfloat *wlp = ssd_global(a.wl) + ao;
-    const unsigned len = (unsigned)c.len;
-    const unsigned tid = threadIdx.x;
+    ssd_state_regs<K, 4> s;
+    ssd_load_state<K, STAGE, PRE, FG, 4>(a, momp, prep, wlp, lane * 4, s);
 
-    if (vec) {
-        const unsigned len4 = len & ~3u;
-        for (unsigned e = tid * 4; e < len4; e += SSD_BLOCK * 4)
-            ssd_fused_elems<K, STAGE, PRE, FG, 4>(a, gp, wp, momp, prep, wlp, e);
-        const unsigned e = len4 + tid;
-        if (e < len) ssd_fused_elems<K, STAGE, PRE, FG, 1>(a, gp, wp, momp, prep, wlp, e);
-    } else {
-        for (unsigned e = tid; e < len; e += SSD_BLOCK)
-            ssd_fused_elems<K, STAGE, PRE, FG, 1>(a, gp, wp, momp, prep, wlp, e);
+    // block -> tensor -> one record {w, first_block, numel, g_0 .. g_{K-1}}
+    const int64_t *rec = a.rec + (int64_t)t * (K + 3);
+    float *w = reinterpret_cast<float *>(rec[0]);
+    const int64_t off = ((int64_t)blockIdx.x - rec[1]) * a.tab.C;
+    const int64_t left = rec[2] - off;
+    const unsigned len = left < (int64_t)a.tab.C ? (unsigned)left : a.tab.C;
+    cgfloat *gp[K];
+    bool vec = ssd_aligned16(w);
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+        const float *g = reinterpret_cast<const float *>(rec[3 + i]);
+        vec = vec && ssd_aligned16(g);
+        gp[i] = ssd_global(g) + off;
+    }
+    gfloat *wp = ssd_global(w) + off;
+
+    unsigned base = 0;
+    for (;;) {
+        ssd_tile<K, STAGE, PRE, FG>(a, gp, wp, momp, prep, wlp, base + lane * 4, len, vec, s);
+        base += SSD_BLOCK * 4;
+        if (base >= len) break; // uniform
+        ssd_load_state<K, STAGE, PRE, FG, 4>(a, momp, prep, wlp, base + lane * 4, s);
     }
 }
 

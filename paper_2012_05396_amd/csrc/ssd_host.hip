@@ -31,7 +31,6 @@ int fail_init(int code, const char *fmt, ...)
     return code;
 }
 
-constexpr int64_t kTensorAlign = 64;  // elements: every tensor starts on 256 B
 constexpr size_t kWsAlign = 256;
 constexpr int kFusedSlots = 8;
 
@@ -44,8 +43,8 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct PtrCache {
     int nslots = 0;
     size_t len = 0;              // pointers per table
-    const float **dev = nullptr; // device [nslots][len] (inside the workspace)
-    const float **host = nullptr; // pinned [nslots][len]
+    int64_t *dev = nullptr;  // device [nslots][len] 8-byte words (inside the workspace)
+    int64_t *host = nullptr; // pinned [nslots][len]
     std::vector<uint64_t> stamp;
     std::vector<char> valid;
     std::vector<hipEvent_t> ev;
@@ -55,11 +54,11 @@ struct PtrCache {
     {
         nslots = n;
         len = l;
-        dev = static_cast<const float **>(dev_mem);
+        dev = static_cast<int64_t *>(dev_mem);
         stamp.assign(n, 0);
         valid.assign(n, 0);
         ev.assign(n, nullptr);
-        hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&host), sizeof(float *) * len * n,
+        hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&host), sizeof(int64_t) * len * n,
                                      hipHostMallocDefault);
         if (e != hipSuccess) {
             host = nullptr;
@@ -79,12 +78,12 @@ struct PtrCache {
         if (host) (void)hipHostFree(host);
         host = nullptr;
     }
-    // key: len pointers.  Returns the device table holding them.
-    hipError_t get(const float *const *key, hipStream_t s, const float *const **out)
+    // key: len words.  Returns the device table holding them.
+    hipError_t get(const int64_t *key, hipStream_t s, const int64_t **out)
     {
         ++clock;
         for (int i = 0; i < nslots; ++i)
-            if (valid[i] && std::memcmp(host + i * len, key, sizeof(float *) * len) == 0) {
+            if (valid[i] && std::memcmp(host + i * len, key, sizeof(int64_t) * len) == 0) {
                 stamp[i] = clock;
                 *out = dev + i * len;
                 return hipSuccess;
@@ -103,8 +102,8 @@ struct PtrCache {
             if (e != hipSuccess) return e;
         }
         valid[lru] = 0;
-        std::memcpy(host + lru * len, key, sizeof(float *) * len);
-        e = hipMemcpyAsync(dev + lru * len, host + lru * len, sizeof(float *) * len,
+        std::memcpy(host + lru * len, key, sizeof(int64_t) * len);
+        e = hipMemcpyAsync(dev + lru * len, host + lru * len, sizeof(int64_t) * len,
                            hipMemcpyHostToDevice, s);
         if (e != hipSuccess) return e;
         e = hipEventRecord(ev[lru], s);
@@ -136,7 +135,7 @@ struct DeviceGuard {
 struct Layout {
     int64_t A = 0;      // elements of one state array that hold tensors
     int64_t stride = 0; // elements from one state array to the next (>= A)
-    std::vector<int64_t> tensor_offset;
+    std::vector<int64_t> tensor_offset, first_block;
     int32_t chunk_elems = 0;
     int64_t num_chunks = 0;
     size_t off_mom = 0, off_pre0 = 0, off_pre1 = 0, off_wl = 0, off_wloc = 0;
@@ -168,16 +167,20 @@ int check_config(const ssd_config *c)
 int make_layout(const ssd_config *c, Layout *L)
 {
     const int T = c->num_tensors, K = c->num_workers;
-    L->tensor_offset.resize(T);
-    int64_t a = 0;
-    for (int t = 0; t < T; ++t) {
-        L->tensor_offset[t] = a;
-        a += (c->numel[t] + kTensorAlign - 1) / kTensorAlign * kTensorAlign;
-    }
-    L->A = a;
     int rc = ssd_plan_chunks(c->numel, T, c->chunk_elems, nullptr, 0, &L->num_chunks, &L->chunk_elems);
     if (rc != SSD_OK) return rc;
     if (L->num_chunks > 0x7fffffffLL) return fail_init(SSD_EINVAL, "model needs %lld chunks, more than one launch holds", (long long)L->num_chunks);
+    // arena: tensor t owns whole blocks of chunk_elems elements, in tensor order
+    L->tensor_offset.resize(T);
+    L->first_block.resize(T);
+    int64_t blocks = 0;
+    for (int t = 0; t < T; ++t) {
+        L->first_block[t] = blocks;
+        L->tensor_offset[t] = blocks * L->chunk_elems;
+        blocks += (c->numel[t] + L->chunk_elems - 1) / L->chunk_elems;
+    }
+    const int64_t a = blocks * L->chunk_elems; // blocks == num_chunks
+    L->A = a;
     size_t o = 0;
     const size_t arr = round_up(sizeof(float) * (size_t)a, kWsAlign);
     L->stride = (int64_t)(arr / sizeof(float));
@@ -188,9 +191,9 @@ int make_layout(const ssd_config *c, Layout *L)
         L->off_wl = o, o += arr * K;
         L->off_wloc = o, o += arr * K;
     }
-    L->off_chunks = o, o += round_up(sizeof(ssd_chunk) * (size_t)L->num_chunks, kWsAlign);
+    L->off_chunks = o, o += round_up(sizeof(int32_t) * (size_t)L->num_chunks, kWsAlign);
     L->off_tensors = o, o += round_up(sizeof(ssd_tensor_desc) * (size_t)T, kWsAlign);
-    L->off_gtab = o, o += round_up(sizeof(float *) * (size_t)T * K, kWsAlign) * kFusedSlots;
+    L->off_gtab = o, o += round_up(sizeof(int64_t) * (size_t)T * (K + 3), kWsAlign) * kFusedSlots;
     L->row_slots = std::max(8, 2 * K);
     L->off_grow = o, o += round_up(sizeof(float *) * (size_t)T, kWsAlign) * L->row_slots;
     L->total = o;
@@ -206,7 +209,7 @@ struct ssd_ctx {
     hipStream_t stream = nullptr;
     char *ws = nullptr;
     float *mom = nullptr, *pre[2] = {nullptr, nullptr}, *wl = nullptr, *wloc = nullptr;
-    ssd_chunk *d_chunks = nullptr;
+    int32_t *d_block_tensor = nullptr;
     ssd_tensor_desc *d_tensors = nullptr;
     PtrCache gtab, grow;
     size_t gtab_stride = 0, grow_stride = 0;
@@ -221,7 +224,7 @@ struct ssd_ctx {
     bool wl_is_global = false, wl_holds_wloc = false;
     int pre_cur = 0;      // which pre_weight array is current
     int pre_written = 0;  // workers that have written the other one this round
-    std::vector<const float *> scratch; // [T*K] transposed pointer table
+    std::vector<int64_t> scratch; // [T][K+3] records: w, first_block, numel, g_0..g_{K-1}
     char err[512];
 
     int fail(int code, const char *fmt, ...)
@@ -242,6 +245,7 @@ struct ssd_ctx {
                        ? (float)((1.0 - (double)h.m) / ((double)h.lr * (double)cfg.delay_k))
                        : 0.0f;
     }
+    ssd_tables tables() const { return ssd_tables{d_block_tensor, d_tensors, (unsigned)L.chunk_elems}; }
     float *arr(float *base, int i) const { return base + (int64_t)i * stride_elems(); }
     int64_t stride_elems() const { return L.stride; }
 };
@@ -348,7 +352,7 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
         c->wl = reinterpret_cast<float *>(c->ws + L.off_wl);
         c->wloc = reinterpret_cast<float *>(c->ws + L.off_wloc);
     }
-    c->d_chunks = reinterpret_cast<ssd_chunk *>(c->ws + L.off_chunks);
+    c->d_block_tensor = reinterpret_cast<int32_t *>(c->ws + L.off_chunks);
     c->d_tensors = reinterpret_cast<ssd_tensor_desc *>(c->ws + L.off_tensors);
     c->h.rescale = cfg->rescale_grad;
     c->h.lr = cfg->lr;
@@ -362,7 +366,12 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
     c->loc_update.assign(K, 0);
     c->has_local.assign(K, 0);
     c->wloc_fresh.assign(K, 0);
-    c->scratch.resize((size_t)T * K);
+    c->scratch.resize((size_t)T * (K + 3));
+    for (int t = 0; t < T; ++t) {
+        c->scratch[(size_t)t * (K + 3) + 0] = (int64_t) reinterpret_cast<uintptr_t>(weights[t]);
+        c->scratch[(size_t)t * (K + 3) + 1] = c->L.first_block[t];
+        c->scratch[(size_t)t * (K + 3) + 2] = c->numel[t];
+    }
 
     DeviceGuard guard(cfg->device);
     if (!guard.ok) {
@@ -380,22 +389,23 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
             return rc;                                                                   \
         }                                                                                \
     } while (0)
-    SSD_INIT_HIP(c->gtab.create(kFusedSlots, (size_t)T * K, c->ws + L.off_gtab), "pointer table (fused)");
+    SSD_INIT_HIP(c->gtab.create(kFusedSlots, (size_t)T * (K + 3), c->ws + L.off_gtab), "pointer table (fused)");
     // slots of the caches are packed at len pointers; the workspace reserves a
     // rounded-up stride per slot, which is at least that
     SSD_INIT_HIP(c->grow.create(L.row_slots, (size_t)T, c->ws + L.off_grow), "pointer table (rows)");
 
-    // chunk table and tensor descriptors: built on the host, uploaded once
-    std::vector<ssd_chunk> chunks((size_t)L.num_chunks);
-    int64_t n = 0;
-    ssd_plan_chunks(c->numel.data(), T, L.chunk_elems, chunks.data(), L.num_chunks, &n, nullptr);
+    // block -> tensor table and tensor descriptors: built on the host, uploaded once
+    std::vector<int32_t> block_tensor((size_t)L.num_chunks);
     std::vector<ssd_tensor_desc> descs(T);
     for (int t = 0; t < T; ++t) {
         descs[t].w = weights[t];
-        descs[t].arena_off = L.tensor_offset[t];
+        descs[t].first_block = L.first_block[t];
+        descs[t].numel = c->numel[t];
+        const int64_t end = t + 1 < T ? L.first_block[t + 1] : L.num_chunks;
+        for (int64_t b = L.first_block[t]; b < end; ++b) block_tensor[(size_t)b] = t;
     }
-    SSD_INIT_HIP(hipMemcpyAsync(c->d_chunks, chunks.data(), sizeof(ssd_chunk) * chunks.size(),
-                                hipMemcpyHostToDevice, c->stream), "upload chunk table");
+    SSD_INIT_HIP(hipMemcpyAsync(c->d_block_tensor, block_tensor.data(), sizeof(int32_t) * block_tensor.size(),
+                                hipMemcpyHostToDevice, c->stream), "upload block table");
     SSD_INIT_HIP(hipMemcpyAsync(c->d_tensors, descs.data(), sizeof(ssd_tensor_desc) * descs.size(),
                                 hipMemcpyHostToDevice, c->stream), "upload tensor table");
     SSD_INIT_HIP(hipStreamSynchronize(c->stream), "upload tables"); // sources are pageable locals
@@ -426,20 +436,20 @@ static int check_grads(ssd_ctx *c, const float *const *const *grads)
             if (!p) return c->fail(SSD_EINVAL, "grads[%d][%d] is NULL", i, t);
             if (reinterpret_cast<uintptr_t>(p) % sizeof(float))
                 return c->fail(SSD_EALIGN, "grads[%d][%d] is not 4-byte aligned", i, t);
-            c->scratch[(size_t)t * K + i] = p;
+            c->scratch[(size_t)t * (K + 3) + 3 + i] = (int64_t) reinterpret_cast<uintptr_t>(p);
         }
     }
     return SSD_OK;
 }
 
 // Resident waves per compute unit that gave the highest HBM throughput when
-// measured on MI355X (sweeps over 3..16 waves; K = 4 and 8 on a 138 M-element
+// measured on MI355X (sweeps over 3..10 waves; K = 4 and 8 on a 138 M-element
 // model, K = 16 on a 60 M-element one).  The optimum is flat within +-1.
 static int default_waves_per_cu(int K, int stage, int from_global)
 {
     if (stage == SSD_STAGE_WARMUP) return 8;       // K+2 read streams, 2 write streams
-    if (!from_global) return 7;                    // 2K+3 read streams, K+2 write streams
-    return K <= 4 ? 7 : 4;                         // K+3 read streams, K+3 write streams
+    if (!from_global) return K <= 4 ? 6 : 5;       // 2K+3 read streams, K+2 write streams
+    return K <= 4 ? 7 : 5;                         // K+3 read streams, K+3 write streams
 }
 
 static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
@@ -449,13 +459,12 @@ static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
         ssd_launch_fused_k5,  ssd_launch_fused_k6,  ssd_launch_fused_k7,  ssd_launch_fused_k8,
         ssd_launch_fused_k9,  ssd_launch_fused_k10, ssd_launch_fused_k11, ssd_launch_fused_k12,
         ssd_launch_fused_k13, ssd_launch_fused_k14, ssd_launch_fused_k15, ssd_launch_fused_k16};
-    const float *const *tab = nullptr;
-    hipError_t e = c->gtab.get(c->scratch.data(), c->stream, &tab);
+    const int64_t *rec = nullptr;
+    hipError_t e = c->gtab.get(c->scratch.data(), c->stream, &rec);
     if (e != hipSuccess) return c->fail_hip(e, "gradient pointer table");
     ssd_fused_args a;
-    a.chunks = c->d_chunks;
-    a.tensors = c->d_tensors;
-    a.gptr = tab;
+    a.tab = c->tables();
+    a.rec = rec;
     a.mom = c->mom;
     a.pre = c->pre[c->pre_cur];
     a.wl = c->wl;
@@ -476,7 +485,7 @@ static int materialize(ssd_ctx *c)
     if (!c->wl_is_global) return SSD_OK;
     const int K = c->cfg.num_workers;
     for (int i = 0; i < K; ++i) {
-        ssd_pull_args a = {c->d_chunks, c->d_tensors, c->arr(c->wl, i), c->arr(c->wloc, i)};
+        ssd_pull_args a = {c->tables(), c->arr(c->wl, i), c->arr(c->wloc, i)};
         hipError_t e = ssd_launch_pull(c->wl_holds_wloc ? 0 : 1, (unsigned)c->L.num_chunks, c->stream, a);
         if (e != hipSuccess) return c->fail_hip(e, "launch of the pull kernel");
         c->wloc_fresh[i] = 1;
@@ -579,13 +588,13 @@ int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const float *const *grads_
     if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
     int rc = materialize(c);
     if (rc != SSD_OK) return rc;
-    const float *const *tab = nullptr;
-    hipError_t e = c->grow.get(grads_i, c->stream, &tab);
+    const int64_t *tab = nullptr;
+    static_assert(sizeof(const float *) == sizeof(int64_t), "pointer tables are tables of 8-byte words");
+    hipError_t e = c->grow.get(reinterpret_cast<const int64_t *>(grads_i), c->stream, &tab);
     if (e != hipSuccess) return c->fail_hip(e, "gradient pointer table");
     ssd_glu_args a;
-    a.chunks = c->d_chunks;
-    a.tensors = c->d_tensors;
-    a.gptr = tab;
+    a.tab = c->tables();
+    a.gptr = reinterpret_cast<const float *const *>(tab);
     a.pre_src = c->pre[c->pre_cur];
     a.pre_dst = c->pre[c->pre_cur ^ 1];
     a.wl = c->arr(c->wl, worker);
@@ -611,7 +620,7 @@ int ssd_worker_pull(ssd_ctx *c, int32_t worker)
     if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
     int rc = materialize(c);
     if (rc != SSD_OK) return rc;
-    ssd_pull_args a = {c->d_chunks, c->d_tensors, c->arr(c->wl, worker), c->arr(c->wloc, worker)};
+    ssd_pull_args a = {c->tables(), c->arr(c->wl, worker), c->arr(c->wloc, worker)};
     hipError_t e = ssd_launch_pull(c->has_local[worker] ? 0 : 1, (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the pull kernel");
     c->has_local[worker] = 1;

@@ -117,10 +117,10 @@ def test_workspace_bytes_rejects_bad_config(kw):
 
 def test_workspace_bytes_counts_the_state_arrays():
     # k = 0: momentum only.  k > 0: momentum, two pre_weight arrays, K local
-    # weights, K w_loc; each array padded per tensor to 64 elements.
+    # weights, K w_loc; every tensor owns whole blocks of 256 elements.
     a = B.ssd_workspace_bytes(_cfg(k=0))
     b = B.ssd_workspace_bytes(_cfg(k=2))
-    arr = (128 + 64) * 4
+    arr = (256 + 256) * 4
     assert b - a == (2 + 2 * 2) * arr
 
 
