@@ -19,7 +19,9 @@ MAX_K = 16
 # is part of the library's contract).  Packed FP32 instructions stay off.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
          "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
+         "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument",
+         # leading kernel arguments arrive in SGPRs at wave launch
+         "-mllvm", "-amdgpu-kernarg-preload-count=14"]
 
 
 def _run(cmd):

@@ -54,11 +54,24 @@ struct ssd_tensor_desc {
     int64_t numel;
 };
 
+// Workgroups are handed to the 8 accelerator dies (XCDs, each with its own L2)
+// round-robin by workgroup id, so the block -> tensor table is stored die-major:
+// entry of block b at (b % 8) * blocks_per_xcd + b / 8.  The 16 entries of one
+// 64-byte line are then used by 16 consecutive workgroups of ONE die instead
+// of being fetched by all eight.
+#define SSD_XCDS 8u
+
 struct ssd_tables {
-    const int32_t *block_tensor;     // [num_blocks]
+    const int32_t *block_tensor;     // [8 * blocks_per_xcd], die-major
     const ssd_tensor_desc *tensors;  // [T]
     unsigned C;                      // elements per block
+    unsigned blocks_per_xcd;         // ceil(num_blocks / 8)
 };
+
+static __host__ __device__ __forceinline__ size_t ssd_block_slot(unsigned b, unsigned blocks_per_xcd)
+{
+    return (size_t)(b % SSD_XCDS) * blocks_per_xcd + b / SSD_XCDS;
+}
 
 struct ssd_block {
     int tensor;
@@ -112,7 +125,7 @@ static __device__ __forceinline__ ssd_block ssd_locate(const ssd_tables &tab, un
                                                        ssd_tensor_desc &td)
 {
     ssd_block k;
-    k.tensor = tab.block_tensor[b];
+    k.tensor = tab.block_tensor[ssd_block_slot(b, tab.blocks_per_xcd)];
     td = tab.tensors[k.tensor];
     k.off = ((int64_t)b - td.first_block) * tab.C;
     const int64_t left = td.numel - k.off;

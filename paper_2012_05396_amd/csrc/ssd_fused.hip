@@ -113,11 +113,29 @@ __device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, cgfloat *const
     }
 }
 
+// The arguments a wave needs first come as separate leading kernel arguments
+// so that they can be preloaded into scalar registers at wave launch
+// (-amdgpu-kernarg-preload-count); the rest arrives with ordinary scalar loads.
 template <int K, int STAGE, int PRE, bool FG>
-__global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const ssd_fused_args a)
+__global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *block_tensor, float *mom,
+                                                              float *pre, float *wl, int64_t A,
+                                                              unsigned C, unsigned blocks_per_xcd,
+                                                              const int64_t *rec_table, const ssd_hyper h)
 {
+    ssd_fused_args a;
+    a.tab.block_tensor = block_tensor;
+    a.tab.tensors = nullptr;
+    a.tab.C = C;
+    a.tab.blocks_per_xcd = blocks_per_xcd;
+    a.rec = rec_table;
+    a.mom = mom;
+    a.pre = pre;
+    a.wl = wl;
+    a.A = A;
+    a.h = h;
     const unsigned lane = threadIdx.x;
-    const int t = a.tab.block_tensor[blockIdx.x]; // head of the lookup chain: request it first
+    // head of the lookup chain: request it first
+    const int t = a.tab.block_tensor[ssd_block_slot(blockIdx.x, a.tab.blocks_per_xcd)];
     // state arrays: addressed by blockIdx alone, always 16-byte aligned, and
     // padded to whole blocks, so the first tile is requested right away
     const int64_t ao = (int64_t)blockIdx.x * a.tab.C;
@@ -164,7 +182,8 @@ hipError_t SSD_CAT(ssd_launch_fused_k, SSD_K)(int stage, int pre_action, int fro
         if (lds > 65536)                                                           \
             (void)hipFuncSetAttribute((const void *)ssd_fused_kernel<SSD_K, ST, PR, FG>,   \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        ssd_fused_kernel<SSD_K, ST, PR, FG><<<grid, block, lds, s>>>(a);           \
+        ssd_fused_kernel<SSD_K, ST, PR, FG><<<grid, block, lds, s>>>(                \
+            a.tab.block_tensor, a.mom, a.pre, a.wl, a.A, a.tab.C, a.tab.blocks_per_xcd, a.rec, a.h); \
         return hipGetLastError();                                                  \
     } while (0)
     if (stage == SSD_STAGE_WARMUP) SSD_GO(SSD_STAGE_WARMUP, SSD_PRE_KEEP, false);

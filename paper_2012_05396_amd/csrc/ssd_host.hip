@@ -137,7 +137,7 @@ struct Layout {
     int64_t stride = 0; // elements from one state array to the next (>= A)
     std::vector<int64_t> tensor_offset, first_block;
     int32_t chunk_elems = 0;
-    int64_t num_chunks = 0;
+    int64_t num_chunks = 0, blocks_per_xcd = 0;
     size_t off_mom = 0, off_pre0 = 0, off_pre1 = 0, off_wl = 0, off_wloc = 0;
     size_t off_chunks = 0, off_tensors = 0, off_gtab = 0, off_grow = 0;
     int row_slots = 0;
@@ -182,7 +182,16 @@ int make_layout(const ssd_config *c, Layout *L)
     const int64_t a = blocks * L->chunk_elems; // blocks == num_chunks
     L->A = a;
     size_t o = 0;
-    const size_t arr = round_up(sizeof(float) * (size_t)a, kWsAlign);
+    // Distance between consecutive state arrays.  Large arrays are placed a
+    // multiple of 64 MiB (2 MiB for mid-sized ones) apart: with the dozens of
+    // streams of the fused kernel walking all arrays at the same relative
+    // position, that placement measured 2-7 % more HBM throughput on MI355X
+    // than arbitrary distances (K = 8 and 16, 100-550 MB arrays).
+    size_t arr = round_up(sizeof(float) * (size_t)a, kWsAlign);
+    if (arr >= ((size_t)64 << 20))
+        arr = round_up(arr, (size_t)64 << 20);
+    else if (arr >= ((size_t)2 << 20))
+        arr = round_up(arr, (size_t)2 << 20);
     L->stride = (int64_t)(arr / sizeof(float));
     L->off_mom = o, o += arr;
     if (c->delay_k > 0) {
@@ -191,7 +200,8 @@ int make_layout(const ssd_config *c, Layout *L)
         L->off_wl = o, o += arr * K;
         L->off_wloc = o, o += arr * K;
     }
-    L->off_chunks = o, o += round_up(sizeof(int32_t) * (size_t)L->num_chunks, kWsAlign);
+    L->blocks_per_xcd = (L->num_chunks + SSD_XCDS - 1) / SSD_XCDS;
+    L->off_chunks = o, o += round_up(sizeof(int32_t) * (size_t)L->blocks_per_xcd * SSD_XCDS, kWsAlign);
     L->off_tensors = o, o += round_up(sizeof(ssd_tensor_desc) * (size_t)T, kWsAlign);
     L->off_gtab = o, o += round_up(sizeof(int64_t) * (size_t)T * (K + 3), kWsAlign) * kFusedSlots;
     L->row_slots = std::max(8, 2 * K);
@@ -245,7 +255,7 @@ struct ssd_ctx {
                        ? (float)((1.0 - (double)h.m) / ((double)h.lr * (double)cfg.delay_k))
                        : 0.0f;
     }
-    ssd_tables tables() const { return ssd_tables{d_block_tensor, d_tensors, (unsigned)L.chunk_elems}; }
+    ssd_tables tables() const { return ssd_tables{d_block_tensor, d_tensors, (unsigned)L.chunk_elems, (unsigned)L.blocks_per_xcd}; }
     float *arr(float *base, int i) const { return base + (int64_t)i * stride_elems(); }
     int64_t stride_elems() const { return L.stride; }
 };
@@ -395,14 +405,15 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
     SSD_INIT_HIP(c->grow.create(L.row_slots, (size_t)T, c->ws + L.off_grow), "pointer table (rows)");
 
     // block -> tensor table and tensor descriptors: built on the host, uploaded once
-    std::vector<int32_t> block_tensor((size_t)L.num_chunks);
+    std::vector<int32_t> block_tensor((size_t)L.blocks_per_xcd * SSD_XCDS, 0);
     std::vector<ssd_tensor_desc> descs(T);
     for (int t = 0; t < T; ++t) {
         descs[t].w = weights[t];
         descs[t].first_block = L.first_block[t];
         descs[t].numel = c->numel[t];
         const int64_t end = t + 1 < T ? L.first_block[t + 1] : L.num_chunks;
-        for (int64_t b = L.first_block[t]; b < end; ++b) block_tensor[(size_t)b] = t;
+        for (int64_t b = L.first_block[t]; b < end; ++b)
+            block_tensor[ssd_block_slot((unsigned)b, (unsigned)L.blocks_per_xcd)] = t;
     }
     SSD_INIT_HIP(hipMemcpyAsync(c->d_block_tensor, block_tensor.data(), sizeof(int32_t) * block_tensor.size(),
                                 hipMemcpyHostToDevice, c->stream), "upload block table");
