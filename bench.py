@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--workers", type=int, default=0, help="override K (not the benchmark configuration)")
     ap.add_argument("--delay", type=int, default=-1, help="override k (not the benchmark configuration)")
+    ap.add_argument("--unfused", action="store_true",
+                    help="time the piecewise calls (server, K x GLU, K x pull) instead of ssd_step")
     ap.add_argument("--pool", type=int, default=2, help="distinct gradient sets cycled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
@@ -140,7 +142,16 @@ def main():
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         e0.record(stream)
-        ctx.ssd_step(tables[it % P])
+        if args.unfused and kind >= 2:
+            # same iteration as separate launches: gradients are read twice
+            ctx.ssd_server_aggregate_update(tables[it % P])
+            for i in range(K):
+                ctx.ssd_worker_glu_update(i, gviews[it % P][i])
+            if kind == 3:
+                for i in range(K):
+                    ctx.ssd_worker_pull(i)
+        else:
+            ctx.ssd_step(tables[it % P])
         e1.record(stream)
         kinds.append((kind, pa, fg))
         events.append((e0, e1))
@@ -185,7 +196,7 @@ def main():
         cpu = cpu_baseline(wl, N, K, k, W, wflat, gsets, offs, numel, args.cpu_sample_elems)
 
     out = {
-        "metric": "param-elements updated/s per full SSD-SGD step",
+        "metric": "param-elements updated/s per full SSD-SGD step" + (" (UNFUSED piecewise calls)" if args.unfused else ""),
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": untimed,
         "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",

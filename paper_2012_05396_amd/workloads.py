@@ -94,6 +94,31 @@ def vgg16():
     return t
 
 
+def alexnet():
+    """AlexNet (single-tower form): five convs with biases, fc 9216-4096-4096-1000."""
+    t = []
+    for i, (cin, cout, ks) in enumerate(((3, 64, 11), (64, 192, 5), (192, 384, 3), (384, 256, 3),
+                                         (256, 256, 3))):
+        _conv(t, "conv%d" % i, cin, cout, ks, bn=False, bias=True)
+    _fc(t, "fc6", 256 * 6 * 6, 4096)
+    _fc(t, "fc7", 4096, 4096)
+    _fc(t, "fc8", 4096, 1000)
+    return t
+
+
+def vgg11():
+    """VGG-11: eight 3x3 convs with biases, then fc 25088-4096-4096-1000."""
+    t = []
+    cin = 3
+    for i, c in enumerate((64, 128, 256, 256, 512, 512, 512, 512)):
+        _conv(t, "conv%d" % i, cin, c, 3, bn=False, bias=True)
+        cin = c
+    _fc(t, "fc6", 512 * 7 * 7, 4096)
+    _fc(t, "fc7", 4096, 4096)
+    _fc(t, "fc8", 4096, 1000)
+    return t
+
+
 def _wl(name, tensors, K, k, steps, **kw):
     d = dict(W=2, lr=0.1, momentum=0.9, wd=1e-4, grad_sigma=1e-2,
              grad_fan_in_scale=False, outlier_p=0.0, outlier_mul=1.0, seed=0)
@@ -116,6 +141,11 @@ def workload(name):
     if name.startswith("resnet152"):
         k = int(name.split("_k")[1]) if "_k" in name else 4
         return _wl(name, imagenet_resnet((3, 8, 36, 3)), 16, k, 20, seed=105)
+    # the communication-intensive models of the paper's Sec. 4.5 (4 workers, 5-step delay)
+    if name == "alexnet":
+        return _wl(name, alexnet(), 4, 5, 20, seed=106)
+    if name == "vgg11":
+        return _wl(name, vgg11(), 4, 5, 20, seed=107)
     raise KeyError(name)
 
 

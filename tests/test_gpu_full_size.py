@@ -22,6 +22,7 @@ from paper_2012_05396_amd import workloads
 pytestmark = pytest.mark.gpu
 
 SAMPLES_PER_TENSOR = 2048
+EXTRA_INDICES = {}   # tensor index -> more element indices to check
 
 
 def sample_indices(numel, chunk, rng):
@@ -43,9 +44,9 @@ def bit_equal(a, b):
     return np.array_equal(a.view(np.int32), b.view(np.int32))
 
 
-def run_full(name, piecewise_check=False):
+def run_full(name, piecewise_check=False, wl=None):
     from paper_2012_05396_amd import binding as B
-    wl = workloads.workload(name)
+    wl = wl or workloads.workload(name)
     dev = torch.device("cuda", 0)
     numel = workloads.numels(wl.tensors)
     T, K, k, W = len(numel), wl.K, wl.k, wl.W
@@ -69,6 +70,8 @@ def run_full(name, piecewise_check=False):
     flat_idx, arena_idx = [], []
     for t in range(T):
         idx = sample_indices(numel[t], v.chunk_elems, rng)
+        if t in EXTRA_INDICES:
+            idx = np.unique(np.concatenate([idx, EXTRA_INDICES[t].astype(np.int64)]))
         flat_idx.append(idx + offs[t])
         arena_idx.append(idx + v.tensor_offset[t])
     flat_idx = torch.from_numpy(np.concatenate(flat_idx)).to(dev)
@@ -176,7 +179,7 @@ def run_full(name, piecewise_check=False):
 
 
 @pytest.mark.parametrize("name", ["resnet20", "resnet56", "resnet50", "vgg16", "resnet152_k2",
-                                  "resnet152_k4", "resnet152_k8"])
+                                  "resnet152_k4", "resnet152_k8", "alexnet", "vgg11"])
 def test_full_size_sampled_parity(name):
     run_full(name)
 
@@ -184,3 +187,25 @@ def test_full_size_sampled_parity(name):
 @pytest.mark.parametrize("name", ["resnet56", "resnet50"])
 def test_full_size_fused_equals_piecewise_everywhere(name):
     run_full(name, piecewise_check=True)
+
+
+def test_tensor_larger_than_2_to_31_elements():
+    """64-bit offsets: one tensor of 2^31 + 1029 elements (8.6 GB per array),
+    sampled at its ends, around block boundaries and at random positions,
+    plus a small second tensor behind it in the arena."""
+    big = 2 ** 31 + 1029
+    free, _ = torch.cuda.mem_get_info()
+    if free < 80 * 2 ** 30:
+        pytest.skip("needs 80 GB of free device memory")
+    tensors = [workloads.TensorSpec("big.weight", (big,), "fc", 4096),
+               workloads.TensorSpec("tail.bias", (77,), "bias", 4096)]
+    wl = workloads._wl("big", tensors, 1, 2, 4, seed=777)
+    rng_extra = np.random.default_rng(3)
+    global EXTRA_INDICES
+    EXTRA_INDICES = {0: np.concatenate([np.arange(2 ** 31 - 6, 2 ** 31 + 6),
+                                        np.arange(2 ** 30 - 3, 2 ** 30 + 3),
+                                        rng_extra.integers(2 ** 31, big, size=512)])}
+    try:
+        run_full("big", wl=wl)
+    finally:
+        EXTRA_INDICES = {}

@@ -168,7 +168,8 @@ def test_bench_refuses_more_than_one_gpu():
 
 def test_workload_shapes_match_the_published_architectures():
     exp = {"resnet20": (272474, 65), "resnet56": (855770, 173), "resnet50": (25557032, 161),
-           "vgg16": (138357544, 32), "resnet152_k4": (60192808, 467)}
+           "vgg16": (138357544, 32), "resnet152_k4": (60192808, 467),
+           "alexnet": (61100840, 16), "vgg11": (132863336, 22)}
     for name, (n, t) in exp.items():
         numel = workloads.numels(workloads.workload(name).tensors)
         assert (sum(numel), len(numel)) == (n, t)
