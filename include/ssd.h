@@ -94,6 +94,9 @@ typedef struct {
     int32_t waves_per_cu;  /* cap on wavefronts resident per compute unit in
                               the fused launch; 0 = the library's measured
                               choice per kernel                               */
+    int32_t grad_sync_exact; /* 0: grad_sync from (pre_weight - w') as printed
+                              in Sec. 3.3; 1: from the exact w_minus of
+                              Sec. 3.2.1, ((1 - lr*wd)*pre_weight - w')       */
 } ssd_config;
 
 /* Device-side state, for inspection.  All arrays are "arena" arrays of
@@ -150,7 +153,8 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace,
 int ssd_server_aggregate_update(ssd_ctx *ctx, const float *const *const *grads);
 
 /* One call of Algorithm 2 (GLU) for one worker, on its local weight w'_i:
- *   grad_sync = (pre_weight - w') * (1-m)/(lr*k)            (Sec. 3.3)
+ *   grad_sync = (pre_weight - w') * (1-m)/(lr*k)            (Sec. 3.3; see
+ *                                         ssd_config.grad_sync_exact)
  *   pre_weight initialised with w' on the worker's first call, refreshed
  *   with w' (value before this update) when loc_update > 0 and
  *   loc_update % k == 0,

@@ -25,6 +25,10 @@
  *     multiply by `rescale` (1/K by default).
  *   - The divisor in grad_sync is always k (Sec. 3.3 prints only lr*k), on
  *     every local update, boundary or not.
+ *   - grad_sync uses (pre_weight - w') as Sec. 3.3 prints it.  The exact
+ *     w_minus of Sec. 3.2.1, ((1 - lr*wd)*pre_weight - w'), is available as a
+ *     variant through pre_scale = 1 - lr*wd (formed in double, then rounded);
+ *     pre_scale = 1 multiplies exactly and gives the default form.
  *   - lr and m inside grad_sync are the server's (Table 1).
  *   - The Pull of Algorithm 1 happens after t <- t+1, so the pulled weight
  *     includes the server update of the same iteration.
@@ -61,6 +65,9 @@ typedef struct {
     REAL lr, m, wd;   /* server: learning rate, momentum, weight decay       */
     REAL lr_loc, alpha, beta, wd_loc; /* worker, Eq. (glu-update)            */
     REAL rescale;     /* factor on the K-sum, 1/K = average                  */
+    REAL pre_scale;   /* factor on pre_weight inside grad_sync: 1 for the form
+                         of Sec. 3.3, (1 - lr*wd) for the exact w_minus of
+                         Sec. 3.2.1                                          */
     long n;           /* elements in the (flattened) model                   */
     long num;         /* Alg. 1: iterations done                             */
     long *loc_update; /* [K] Alg. 2: local updates done by worker i          */
@@ -90,6 +97,12 @@ void NAME(ssd_oracle_server)(long n, int K, const REAL *const *g, REAL rescale,
     }
 }
 
+/* The factor (1 - lr*wd) of the exact w_minus (Sec. 3.2.1), formed in double. */
+REAL NAME(ssd_oracle_pre_scale)(REAL lr, REAL wd)
+{
+    return (REAL)(1.0 - (double)lr * (double)wd);
+}
+
 /* The factor (1-m)/(lr*k) of Sec. 3.3, formed once in double. */
 REAL NAME(ssd_oracle_c_sync)(REAL lr, REAL m, int k)
 {
@@ -99,15 +112,16 @@ REAL NAME(ssd_oracle_c_sync)(REAL lr, REAL m, int k)
 /* One call of Algorithm 2 for one worker: wl, pre are that worker's arrays,
  * *loc_update its counter.  */
 void NAME(ssd_oracle_glu)(long n, int k, const REAL *g, REAL *wl, REAL *pre,
-                          long *loc_update, REAL c_sync, REAL lr_loc,
-                          REAL alpha, REAL beta, REAL wd_loc)
+                          long *loc_update, REAL c_sync, REAL pre_scale,
+                          REAL lr_loc, REAL alpha, REAL beta, REAL wd_loc)
 {
     long lu = *loc_update;
     int refresh = (lu > 0) && (lu % k == 0);
     for (long j = 0; j < n; ++j) {
         if (lu == 0)
             pre[j] = wl[j];             /* Alg. 2 initialisation             */
-        REAL e = pre[j] - wl[j];
+        REAL q = pre_scale * pre[j];    /* pre_scale = 1: q is pre_weight    */
+        REAL e = q - wl[j];
         REAL gs = e * c_sync;           /* grad_sync, Sec. 3.3               */
         if (refresh)
             pre[j] = wl[j];             /* Alg. 2: pre_weight = w'           */
@@ -170,8 +184,8 @@ int NAME(ssd_oracle_step)(NAME(ssd_oracle_state) *s, const REAL *const *g)
         for (int i = 0; i < K; ++i)
             NAME(ssd_oracle_glu)(n, s->k, g[i], s->wl + (size_t)i * n,
                                  s->pre + (size_t)i * n, &s->loc_update[i],
-                                 c_sync, s->lr_loc, s->alpha, s->beta,
-                                 s->wd_loc);
+                                 c_sync, s->pre_scale, s->lr_loc, s->alpha,
+                                 s->beta, s->wd_loc);
         /* Broadcast w' to the devices, and every k-th iteration Pull.      */
         for (int i = 0; i < K; ++i)
             copy_n(n, s->wl + (size_t)i * n, s->wloc + (size_t)i * n);

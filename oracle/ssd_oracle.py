@@ -30,7 +30,7 @@ def _state_struct(real):
         _fields_ = [("K", C.c_int), ("k", C.c_int), ("W", C.c_int),
                     ("lr", real), ("m", real), ("wd", real),
                     ("lr_loc", real), ("alpha", real), ("beta", real),
-                    ("wd_loc", real), ("rescale", real),
+                    ("wd_loc", real), ("rescale", real), ("pre_scale", real),
                     ("n", C.c_long), ("num", C.c_long),
                     ("loc_update", C.POINTER(C.c_long)),
                     ("w", C.c_void_p), ("mom", C.c_void_p),
@@ -50,7 +50,7 @@ class Oracle:
     """
 
     def __init__(self, w0, K, k, W, lr, m, wd, lr_loc=None, alpha=2.0,
-                 beta=0.5, wd_loc=None, rescale=None, mode="f64"):
+                 beta=0.5, wd_loc=None, rescale=None, exact_w_minus=False, mode="f64"):
         assert mode in ("f32", "f64")
         self.mode = mode
         self.dtype = np.float32 if mode == "f32" else np.float64
@@ -66,6 +66,7 @@ class Oracle:
         w0 = np.ascontiguousarray(np.asarray(w0).reshape(-1))
         n = w0.size
         self.K, self.k, self.W, self.n = int(K), int(k), int(W), n
+        self.exact_w_minus = bool(exact_w_minus)
         self.w = w0.astype(self.dtype).copy()
         self.mom = np.zeros(n, self.dtype)
         self.wl = np.zeros((K, n), self.dtype)
@@ -75,14 +76,23 @@ class Oracle:
         S = _state_struct(self.real)
         self.s = S(K=K, k=k, W=W, lr=f32(lr), m=f32(m), wd=f32(wd),
                    lr_loc=f32(lr_loc), alpha=f32(alpha), beta=f32(beta),
-                   wd_loc=f32(wd_loc), rescale=f32(rescale), n=n, num=0,
+                   wd_loc=f32(wd_loc), rescale=f32(rescale), pre_scale=1.0, n=n, num=0,
                    loc_update=self.loc_update,
                    w=self.w.ctypes.data, mom=self.mom.ctypes.data,
                    wl=self.wl.ctypes.data, pre=self.pre.ctypes.data,
                    wloc=self.wloc.ctypes.data)
         self._step = getattr(self.lib, "ssd_oracle_step_" + mode)
         self._step.restype = C.c_int
+        self._set_pre_scale()
         getattr(self.lib, "ssd_oracle_begin_" + mode)(C.byref(self.s))
+
+    def _set_pre_scale(self):
+        if self.exact_w_minus:
+            f = getattr(self.lib, "ssd_oracle_pre_scale_" + self.mode)
+            f.restype = self.real
+            self.s.pre_scale = f(self.real(self.s.lr), self.real(self.s.wd))
+        else:
+            self.s.pre_scale = 1.0
 
     def _gptrs(self, grads):
         keep = [np.ascontiguousarray(np.asarray(g).reshape(-1), self.dtype)
@@ -99,6 +109,7 @@ class Oracle:
     def set_lr(self, lr, lr_loc):
         self.s.lr = float(np.float32(lr))
         self.s.lr_loc = float(np.float32(lr_loc))
+        self._set_pre_scale()
 
     @property
     def num(self):
@@ -136,7 +147,7 @@ class Oracle:
         f(C.c_long(self.n), C.c_int(self.k), C.c_void_p(g.ctypes.data),
           C.c_void_p(self.wl[i].ctypes.data),
           C.c_void_p(self.pre[i].ctypes.data), C.byref(lu),
-          r(self.c_sync()), r(self.s.lr_loc), r(self.s.alpha),
+          r(self.c_sync()), r(self.s.pre_scale), r(self.s.lr_loc), r(self.s.alpha),
           r(self.s.beta), r(self.s.wd_loc))
         self.loc_update[i] = lu.value
 

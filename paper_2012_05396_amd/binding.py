@@ -27,7 +27,8 @@ class ssd_config(C.Structure):
                 ("num_tensors", C.c_int32),
                 ("numel", C.POINTER(C.c_int64)),
                 ("device", C.c_int32), ("stream", C.c_void_p),
-                ("chunk_elems", C.c_int32), ("waves_per_cu", C.c_int32)]
+                ("chunk_elems", C.c_int32), ("waves_per_cu", C.c_int32),
+                ("grad_sync_exact", C.c_int32)]
 
 
 class ssd_state_view(C.Structure):
@@ -119,7 +120,8 @@ def ssd_probe_copy(src, dst, stream=None):
 
 
 def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=2.0, beta=0.5, wd_loc=None,
-                rescale_grad=None, device=0, stream=None, chunk_elems=0, waves_per_cu=0):
+                rescale_grad=None, device=0, stream=None, chunk_elems=0, waves_per_cu=0,
+                grad_sync_exact=0):
     """ssd_config with the defaults of Sec. 4.1 of the paper (loc_lr = 4*lr,
     alpha = 2, beta = 0.5) and the averaged gradient (1/K).  Returns the
     struct; it keeps the numel array alive."""
@@ -132,7 +134,8 @@ def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=2.0, beta=0
         alpha=alpha, beta=beta, wd_loc=wd if wd_loc is None else wd_loc,
         rescale_grad=float(np.float32(1.0 / max(K, 1))) if rescale_grad is None else rescale_grad,
         num_tensors=T, numel=arr, device=device,
-        stream=stream, chunk_elems=chunk_elems, waves_per_cu=waves_per_cu)
+        stream=stream, chunk_elems=chunk_elems, waves_per_cu=waves_per_cu,
+        grad_sync_exact=grad_sync_exact)
     cfg._keep = arr
     return cfg
 

@@ -8,7 +8,7 @@
 //     S = g_0; S = S + g_i (i = 1..K-1); gh = S*rescale; t1 = wd*w;
 //     t2 = gh + t1; t3 = lr*t2; t4 = m*mom; mom' = t4 - t3; w' = w + mom'
 //   GLU (Eq. (glu-update), grad_sync of Sec. 3.3, descent sign):
-//     e = pre - wl; gs = e*c_sync; u1 = alpha*g; u2 = wd_loc*wl; u3 = u1 + u2;
+//     q = pre_scale*pre; e = q - wl; gs = e*c_sync; u1 = alpha*g; u2 = wd_loc*wl; u3 = u1 + u2;
 //     u4 = beta*gs; u5 = u3 + u4; u6 = lr_loc*u5; wl' = wl - u6
 #pragma once
 #include <hip/hip_runtime.h>
@@ -83,6 +83,7 @@ struct ssd_block {
 struct ssd_hyper {
     float rescale, lr, m, wd;                    // server
     float c_sync, lr_loc, alpha, beta, wd_loc;   // worker
+    float pre_scale;                             // 1, or 1 - lr*wd for the exact w_minus
 };
 
 struct ssd_fused_args {
@@ -149,7 +150,8 @@ __device__ __forceinline__ void ssd_server_elem(float S, float w, float mom, con
 
 __device__ __forceinline__ float ssd_glu_elem(float g, float wl, float pre, const ssd_hyper &h)
 {
-    float e = pre - wl;
+    float q = h.pre_scale * pre;
+    float e = q - wl;
     float gs = e * h.c_sync;
     float u1 = h.alpha * g;
     float u2 = h.wd_loc * wl;

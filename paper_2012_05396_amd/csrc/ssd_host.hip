@@ -159,6 +159,8 @@ int check_config(const ssd_config *c)
         return fail_init(SSD_EINVAL, "lr = 0 with delay_k > 0: grad_sync divides by lr*k");
     if (c->chunk_elems < 0 || c->chunk_elems % 256 != 0)
         return fail_init(SSD_EINVAL, "chunk_elems = %d, must be 0 or a positive multiple of 256", c->chunk_elems);
+    if (c->grad_sync_exact != 0 && c->grad_sync_exact != 1)
+        return fail_init(SSD_EINVAL, "grad_sync_exact = %d, must be 0 or 1", c->grad_sync_exact);
     if (c->waves_per_cu < 0) return fail_init(SSD_EINVAL, "waves_per_cu = %d, must be >= 0", c->waves_per_cu);
     if (c->device < 0) return fail_init(SSD_EINVAL, "device = %d", c->device);
     return SSD_OK;
@@ -254,6 +256,8 @@ struct ssd_ctx {
         h.c_sync = cfg.delay_k > 0
                        ? (float)((1.0 - (double)h.m) / ((double)h.lr * (double)cfg.delay_k))
                        : 0.0f;
+        // exact w_minus of Sec. 3.2.1: ((1 - lr*wd)*pre_weight - w'); else the factor is 1
+        h.pre_scale = cfg.grad_sync_exact ? (float)(1.0 - (double)h.lr * (double)h.wd) : 1.0f;
     }
     ssd_tables tables() const { return ssd_tables{d_block_tensor, d_tensors, (unsigned)L.chunk_elems, (unsigned)L.blocks_per_xcd}; }
     float *arr(float *base, int i) const { return base + (int64_t)i * stride_elems(); }

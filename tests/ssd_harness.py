@@ -141,6 +141,8 @@ def run_schedule(numel, K, k, W, steps, hp=None, mode="f32", chunk_elems=256, se
             ohp[a] = hp[a]
     if "rescale_grad" in hp:
         ohp["rescale"] = hp["rescale_grad"]
+    if hp.get("grad_sync_exact"):
+        ohp["exact_w_minus"] = True
     o = Oracle(model.w0, K=K, k=k, W=W, mode=mode, **ohp)
     tables = [B.GradTable(g) for g in model.g_dev]
     exact = mode == "f32"

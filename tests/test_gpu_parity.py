@@ -223,3 +223,17 @@ def test_mixed_fused_and_piecewise_iterations():
             pass
         compare_state(ctx, m, o, exact=True, where="mixed it=%d %s" % (it, how))
     ctx.close()
+
+
+@pytest.mark.parametrize("hp", [
+    dict(lr=0.1, momentum=0.9, wd=1e-2, grad_sync_exact=1),                          # exact w_minus
+    dict(lr=0.1, momentum=0.9, wd=1e-4, lr_loc=0.1, alpha=1.0, beta=0.0, wd_loc=0.0),  # plain local SGD
+    dict(lr=0.1, momentum=0.9, wd=1e-4, alpha=0.0, beta=0.0),                        # pure decay
+])
+def test_local_updater_variants_bit_exact(hp):
+    """Variants of the local updater the paper describes: grad_sync from the
+    exact w_minus of Sec. 3.2.1; Eq. (worker) (alpha = 1, beta = 0, no decay);
+    and the degenerate alpha = beta = 0."""
+    print("case: local updater variant %r" % (hp,), flush=True)
+    run_schedule(ODD, K=4, k=3, W=2, steps=2 + 8, hp=hp, seed=13,
+                 lr_changes={6: (0.05, 0.2)} if hp.get("grad_sync_exact") else None)

@@ -521,3 +521,47 @@ def test_piecewise_calls_equal_step():
         else:
             for name in ("w", "mom", "wl", "pre"):
                 assert np.array_equal(getattr(a, name), getattr(b, name)), name
+
+
+# ---------------------------------------------------------------------------
+# variant: grad_sync from the exact w_minus of Sec. 3.2.1
+# ---------------------------------------------------------------------------
+def test_exact_w_minus_follows_identity_of_section_3_2_1():
+    """k = 1: at every local update after the first, pre_weight is w_{j-1} and
+    w' is w_j (pulled one iteration earlier), so by the identity of Sec. 3.2.1
+      (1 - lr*wd)*w_{j-1} - w_j = lr*grad_{j-1} - m*mom_{j-2}
+    the exact grad_sync equals (lr*grad - m*mom_prev)*(1-m)/lr, a quantity of
+    the server alone.  alpha = 0, wd_loc = 0, beta = 1, lr_loc = 1 expose it:
+    w_loc = w' - grad_sync."""
+    rng = np.random.default_rng(71)
+    n, K, W = 11, 2, 3
+    lr, m, wd = f32(0.1), f32(0.9), f32(0.05)
+    o = Oracle(rng.standard_normal(n).astype(np.float32), K=K, k=1, W=W, lr=lr, m=m, wd=wd,
+               lr_loc=1.0, alpha=0.0, beta=1.0, wd_loc=0.0, exact_w_minus=True, mode="f64")
+    prev = None      # (averaged gradient, momentum before the step) of the previous iteration
+    for it in range(W + 6):
+        g = rand_grads(rng, K, n, 1.0)
+        gbar = np.mean(np.stack(g).astype(np.float64), axis=0)
+        mom_before = o.mom.copy()
+        wl_before = o.wl.copy()
+        o.step(g)
+        if it > W:   # d >= 1
+            gbar_prev, mom_prev = prev
+            exp = (lr * gbar_prev - m * mom_prev) * (1 - m) / lr
+            np.testing.assert_allclose(wl_before[0] - o.wloc[0], exp, rtol=1e-9, atol=1e-12)
+        prev = (gbar, mom_before)
+
+
+def test_exact_w_minus_differs_from_default_only_by_the_decay_term():
+    """With wd = 0 the two forms coincide bit for bit; with wd > 0 they differ."""
+    rng = np.random.default_rng(72)
+    n, K, k, W = 30, 2, 2, 2
+    w0 = rng.standard_normal(n).astype(np.float32)
+    gs = [rand_grads(rng, K, n) for _ in range(W + 5)]
+    for wd, same in ((0.0, True), (1e-2, False)):
+        a = Oracle(w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=wd, wd_loc=0.0, mode="f32")
+        b = Oracle(w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=wd, wd_loc=0.0, exact_w_minus=True, mode="f32")
+        for g in gs:
+            a.step(g); b.step(g)
+        assert np.array_equal(a.w, b.w)                       # the server never depends on it
+        assert np.array_equal(a.wl, b.wl) == same
