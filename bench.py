@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--delay", type=int, default=-1, help="override k (not the benchmark configuration)")
     ap.add_argument("--unfused", action="store_true",
                     help="time the piecewise calls (server, K x GLU, K x pull) instead of ssd_step")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="with --unfused: server update and local updates on two streams, ordered by "
+                         "events only where Algorithm 1 has a data dependency")
     ap.add_argument("--pool", type=int, default=2, help="distinct gradient sets cycled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
@@ -134,6 +137,11 @@ def main():
 
     kinds, events = [], []
     d = it - W
+    pulls_done = None
+    if args.two_streams:
+        ctx.ssd_materialize()
+        torch.cuda.synchronize()
+        s_srv, s_wrk = torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -142,7 +150,24 @@ def main():
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         e0.record(stream)
-        if args.unfused and kind >= 2:
+        if args.unfused and kind >= 2 and args.two_streams:
+            ctx.ssd_set_stream(s_srv)
+            if pulls_done is not None:
+                s_srv.wait_event(pulls_done)
+                pulls_done = None
+            ctx.ssd_server_aggregate_update(tables[it % P])
+            srv_done = torch.cuda.Event()
+            srv_done.record(s_srv)
+            ctx.ssd_set_stream(s_wrk)
+            for i in range(K):
+                ctx.ssd_worker_glu_update(i, gviews[it % P][i])
+            if kind == 3:
+                s_wrk.wait_event(srv_done)
+                for i in range(K):
+                    ctx.ssd_worker_pull(i)
+                pulls_done = torch.cuda.Event()
+                pulls_done.record(s_wrk)
+        elif args.unfused and kind >= 2:
             # same iteration as separate launches: gradients are read twice
             ctx.ssd_server_aggregate_update(tables[it % P])
             for i in range(K):

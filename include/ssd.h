@@ -192,6 +192,16 @@ int ssd_materialize(ssd_ctx *ctx);
  * from the next call on. */
 int ssd_set_lr(ssd_ctx *ctx, float lr, float lr_loc);
 
+/* Enqueue the following calls on another stream (NULL = the default stream).
+ * The library adds no synchronisation between streams except for its own
+ * pointer tables: work on different streams that touches the same arrays --
+ * e.g. the server update of the next iteration against a Pull still reading
+ * the global weight -- must be ordered by the caller with events.  This is
+ * what lets the server update and the local updates of one iteration run
+ * side by side, as in the execution order of the paper's Fig. 3(b) (Push and
+ * local update only read the gradient). */
+int ssd_set_stream(ssd_ctx *ctx, void *stream);
+
 /* Fill *out (host).  Does not synchronise. */
 int ssd_get_state(ssd_ctx *ctx, ssd_state_view *out);
 

@@ -62,6 +62,7 @@ def _load():
         "ssd_step": (C.c_int, [C.c_void_p, P(C.c_void_p)]),
         "ssd_materialize": (C.c_int, [C.c_void_p]),
         "ssd_set_lr": (C.c_int, [C.c_void_p, C.c_float, C.c_float]),
+        "ssd_set_stream": (C.c_int, [C.c_void_p, C.c_void_p]),
         "ssd_get_state": (C.c_int, [C.c_void_p, P(ssd_state_view)]),
         "ssd_last_error": (C.c_char_p, [C.c_void_p]),
         "ssd_destroy": (None, [C.c_void_p]),
@@ -214,6 +215,11 @@ class Context:
 
     def ssd_set_lr(self, lr, lr_loc):
         _check(lib.ssd_set_lr(self.h, lr, lr_loc), self.h)
+
+    def ssd_set_stream(self, stream):
+        """stream: a torch.cuda.Stream, a raw hipStream_t value, or None."""
+        raw = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+        _check(lib.ssd_set_stream(self.h, C.c_void_p(raw)), self.h)
 
     def ssd_get_state(self):
         v = ssd_state_view()

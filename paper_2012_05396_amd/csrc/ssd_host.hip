@@ -48,6 +48,7 @@ struct PtrCache {
     std::vector<uint64_t> stamp;
     std::vector<char> valid;
     std::vector<hipEvent_t> ev;
+    std::vector<hipStream_t> up_stream; // stream each slot was uploaded on
     uint64_t clock = 0;
 
     hipError_t create(int n, size_t l, void *dev_mem)
@@ -58,6 +59,7 @@ struct PtrCache {
         stamp.assign(n, 0);
         valid.assign(n, 0);
         ev.assign(n, nullptr);
+        up_stream.assign(n, nullptr);
         hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&host), sizeof(int64_t) * len * n,
                                      hipHostMallocDefault);
         if (e != hipSuccess) {
@@ -86,6 +88,10 @@ struct PtrCache {
             if (valid[i] && std::memcmp(host + i * len, key, sizeof(int64_t) * len) == 0) {
                 stamp[i] = clock;
                 *out = dev + i * len;
+                if (up_stream[i] != s) { // uploaded on another stream: order this one after it
+                    hipError_t e = hipStreamWaitEvent(s, ev[i], 0);
+                    if (e != hipSuccess) return e;
+                }
                 return hipSuccess;
             }
         int lru = -1;
@@ -109,6 +115,7 @@ struct PtrCache {
         e = hipEventRecord(ev[lru], s);
         if (e != hipSuccess) return e;
         valid[lru] = 1;
+        up_stream[lru] = s;
         stamp[lru] = clock;
         *out = dev + lru * len;
         return hipSuccess;
@@ -650,6 +657,13 @@ int ssd_set_lr(ssd_ctx *c, float lr, float lr_loc)
     c->h.lr = lr;
     c->h.lr_loc = lr_loc;
     c->set_c_sync();
+    return SSD_OK;
+}
+
+int ssd_set_stream(ssd_ctx *c, void *stream)
+{
+    if (!c) return SSD_EINVAL;
+    c->stream = static_cast<hipStream_t>(stream);
     return SSD_OK;
 }
 

@@ -237,3 +237,51 @@ def test_local_updater_variants_bit_exact(hp):
     print("case: local updater variant %r" % (hp,), flush=True)
     run_schedule(ODD, K=4, k=3, W=2, steps=2 + 8, hp=hp, seed=13,
                  lr_changes={6: (0.05, 0.2)} if hp.get("grad_sync_exact") else None)
+
+
+def test_two_stream_schedule_of_fig_3b():
+    """Server update on one stream, local updates (and Pulls) on another, with
+    events only where Algorithm 1 has a data dependency: a Pull reads the
+    global weight after this iteration's server update, and the next server
+    update must not overwrite it before the Pulls have read it."""
+    print("case: two streams", flush=True)
+    from oracle.ssd_oracle import Oracle
+    from paper_2012_05396_amd import binding as B
+    numel, K, k, W = [70000, 513, 64, 1025], 4, 2, 1
+    m = Model(numel, K, seed=41)
+    main = torch.cuda.current_stream()
+    s_srv, s_wrk = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-4, stream=main.cuda_stream), m.weights)
+    o = Oracle(m.w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=1e-4, mode="f32")
+    ctx.ssd_step(m.g_dev[0])                    # warm-up (also the last warm-up iteration)
+    o.step(m.g_host[0])
+    ctx.ssd_materialize()
+    ready = torch.cuda.Event()
+    ready.record(main)
+    s_srv.wait_event(ready)
+    s_wrk.wait_event(ready)
+    pulls_done = None
+    for d in range(3 * k + 1):
+        p = (d + 1) % 3
+        ctx.ssd_set_stream(s_srv)
+        if pulls_done is not None:
+            s_srv.wait_event(pulls_done)        # Pulls of the previous iteration read w
+            pulls_done = None
+        ctx.ssd_server_aggregate_update(m.g_dev[p])
+        srv_done = torch.cuda.Event()
+        srv_done.record(s_srv)
+        ctx.ssd_set_stream(s_wrk)
+        for i in range(K):
+            ctx.ssd_worker_glu_update(i, m.g_dev[p][i])
+        if d % k == k - 1:
+            s_wrk.wait_event(srv_done)          # Pull w_t: after this iteration's server update
+            for i in range(K):
+                ctx.ssd_worker_pull(i)
+            pulls_done = torch.cuda.Event()
+            pulls_done.record(s_wrk)
+        o.step(m.g_host[p])
+        if d in (k, 3 * k):                     # elsewhere the two streams keep running freely
+            torch.cuda.synchronize()
+            compare_state(ctx, m, o, exact=True, where="two streams d=%d" % d)
+    ctx.ssd_set_stream(main)
+    ctx.close()
