@@ -465,13 +465,21 @@ static int check_grads(ssd_ctx *c, const float *const *const *grads)
 }
 
 // Resident waves per compute unit that gave the highest HBM throughput when
-// measured on MI355X (sweeps over 3..10 waves; K = 4 and 8 on a 138 M-element
-// model, K = 16 on a 60 M-element one).  The optimum is flat within +-1.
+// measured on MI355X: sweeps over 3..16 waves for K = 1, 2, 4, 8 on 133-138 M-
+// element models and K = 16 on a 60 M-element one.  The best cap falls as a
+// wave carries more streams -- roughly a constant number of KiB requested per
+// compute unit -- and never goes below 4; the optimum is flat within +-1.
 static int default_waves_per_cu(int K, int stage, int from_global)
 {
-    if (stage == SSD_STAGE_WARMUP) return 8;       // K+2 read streams, 2 write streams
-    if (!from_global) return K <= 4 ? 6 : 5;       // 2K+3 read streams, K+2 write streams
-    return K <= 4 ? 7 : 5;                         // K+3 read streams, K+3 write streams
+    int loads, budget; // 128-bit loads per lane, KiB in flight per compute unit
+    if (stage == SSD_STAGE_WARMUP)
+        loads = K + 2, budget = 80;
+    else if (from_global)
+        loads = K + 3, budget = 60;
+    else
+        loads = 2 * K + 3, budget = 56;
+    const int n = (budget + loads / 2) / loads;
+    return n < 4 ? 4 : (n > 16 ? 16 : n);
 }
 
 static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
