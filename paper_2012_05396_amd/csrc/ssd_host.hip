@@ -1,9 +1,10 @@
 // Host side of the SSD-SGD library: argument checks, the schedule of
-// Algorithm 1 / Algorithm 2 of the paper as a small state machine, the chunk
-// table of the multi-tensor launch, gradient-pointer tables, and the launches.
-// No arithmetic of the method runs here except the two configuration
-// constants c_sync = (1-m)/(lr*k) (Sec. 3.3) which is formed once per
-// learning-rate change in binary64 and rounded to binary32.
+// Algorithm 1 / Algorithm 2 of the paper as a small state machine, the block
+// and pointer tables of the multi-tensor launch, and the launches.
+// No arithmetic of the method runs here except two configuration constants,
+// c_sync = (1-m)/(lr*k) (Sec. 3.3) and, for the exact-w_minus variant,
+// 1 - lr*wd (Sec. 3.2.1), formed once per learning-rate change in binary64
+// and rounded to binary32.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -11,7 +12,6 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
-#include <string>
 #include <vector>
 
 #include "ssd_device.h"
@@ -48,7 +48,8 @@ struct PtrCache {
     std::vector<uint64_t> stamp;
     std::vector<char> valid;
     std::vector<hipEvent_t> ev;
-    std::vector<hipStream_t> up_stream; // stream each slot was uploaded on
+    std::vector<hipStream_t> up_stream;  // stream each slot was uploaded on
+    std::vector<hipStream_t> use_stream; // stream of the last launch that read the slot
     uint64_t clock = 0;
 
     hipError_t create(int n, size_t l, void *dev_mem)
@@ -60,6 +61,7 @@ struct PtrCache {
         valid.assign(n, 0);
         ev.assign(n, nullptr);
         up_stream.assign(n, nullptr);
+        use_stream.assign(n, nullptr);
         hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&host), sizeof(int64_t) * len * n,
                                      hipHostMallocDefault);
         if (e != hipSuccess) {
@@ -92,6 +94,7 @@ struct PtrCache {
                     hipError_t e = hipStreamWaitEvent(s, ev[i], 0);
                     if (e != hipSuccess) return e;
                 }
+                use_stream[i] = s;
                 return hipSuccess;
             }
         int lru = -1;
@@ -106,6 +109,10 @@ struct PtrCache {
         if (valid[lru]) {
             e = hipEventSynchronize(ev[lru]); // staging copy may still be queued
             if (e != hipSuccess) return e;
+            if (use_stream[lru] != s) { // a launch on another stream may still read the old table
+                e = hipStreamSynchronize(use_stream[lru]);
+                if (e != hipSuccess) return e;
+            }
         }
         valid[lru] = 0;
         std::memcpy(host + lru * len, key, sizeof(int64_t) * len);
@@ -116,6 +123,7 @@ struct PtrCache {
         if (e != hipSuccess) return e;
         valid[lru] = 1;
         up_stream[lru] = s;
+        use_stream[lru] = s;
         stamp[lru] = clock;
         *out = dev + lru * len;
         return hipSuccess;
@@ -231,7 +239,6 @@ struct ssd_ctx {
     int32_t *d_block_tensor = nullptr;
     ssd_tensor_desc *d_tensors = nullptr;
     PtrCache gtab, grow;
-    size_t gtab_stride = 0, grow_stride = 0;
     ssd_hyper h;
     int64_t it = 0;
     std::vector<int64_t> loc_update;
