@@ -192,6 +192,15 @@ int ssd_materialize(ssd_ctx *ctx);
  * from the next call on. */
 int ssd_set_lr(ssd_ctx *ctx, float lr, float lr_loc);
 
+/* Per-tensor multipliers, as optimisers of deep-learning frameworks keep them
+ * (e.g. no weight decay on biases and normalisation parameters; the paper is
+ * silent on them): tensor t uses lr*lr_mult[t] and lr_loc*lr_mult[t] as its
+ * learning rates (also inside grad_sync) and wd*wd_mult[t], wd_loc*wd_mult[t]
+ * as its weight decays, each product one binary32 multiplication.  Host arrays
+ * [T], values >= 0; NULL = all ones.  A tensor with lr_mult 0 is frozen and
+ * its grad_sync is 0.  Takes effect for the calls that follow. */
+int ssd_set_tensor_multipliers(ssd_ctx *ctx, const float *lr_mult, const float *wd_mult);
+
 /* Enqueue the following calls on another stream (NULL = the default stream).
  * The library adds no synchronisation between streams except for its own
  * pointer tables: work on different streams that touches the same arrays --

@@ -63,6 +63,7 @@ def _load():
         "ssd_materialize": (C.c_int, [C.c_void_p]),
         "ssd_set_lr": (C.c_int, [C.c_void_p, C.c_float, C.c_float]),
         "ssd_set_stream": (C.c_int, [C.c_void_p, C.c_void_p]),
+        "ssd_set_tensor_multipliers": (C.c_int, [C.c_void_p, P(C.c_float), P(C.c_float)]),
         "ssd_get_state": (C.c_int, [C.c_void_p, P(ssd_state_view)]),
         "ssd_last_error": (C.c_char_p, [C.c_void_p]),
         "ssd_destroy": (None, [C.c_void_p]),
@@ -215,6 +216,10 @@ class Context:
 
     def ssd_set_lr(self, lr, lr_loc):
         _check(lib.ssd_set_lr(self.h, lr, lr_loc), self.h)
+
+    def ssd_set_tensor_multipliers(self, lr_mult=None, wd_mult=None):
+        conv = lambda m: None if m is None else (C.c_float * self.T)(*[float(x) for x in m])
+        _check(lib.ssd_set_tensor_multipliers(self.h, conv(lr_mult), conv(wd_mult)), self.h)
 
     def ssd_set_stream(self, stream):
         """stream: a torch.cuda.Stream, a raw hipStream_t value, or None."""

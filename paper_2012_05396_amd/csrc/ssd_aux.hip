@@ -16,7 +16,7 @@ __device__ __forceinline__ void ssd_glu_elems(const ssd_hyper &h, cgfloat *gp, g
 #pragma unroll
     for (int v = 0; v < VW; ++v) {
         float pv = (PRE == SSD_PRE_INIT) ? wl[v] : p[v];
-        r[v] = ssd_glu_elem(g[v], wl[v], pv, h);
+        r[v] = ssd_glu_elem<true>(g[v], wl[v], pv, h); // pre_scale is 1 unless the variant is on
     }
     if (PRE != SSD_PRE_KEEP) V::st(predst + e, wl);
     V::st(wlp + e, r);
@@ -34,15 +34,16 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_glu_kernel(const ssd_glu_args a
     cgfloat *presrc = ssd_global(a.pre_src) + blk.ao;
     gfloat *predst = ssd_global(a.pre_dst) + blk.ao;
     const unsigned len = blk.len, tid = threadIdx.x;
+    const ssd_hyper h = ssd_hyper_of(a.h, a.thyper[blk.tensor]);
     if (vec) {
         const unsigned len4 = len & ~3u;
         for (unsigned e = tid * 4; e < len4; e += SSD_BLOCK * 4)
-            ssd_glu_elems<PRE, 4>(a.h, gp, wlp, presrc, predst, e);
+            ssd_glu_elems<PRE, 4>(h, gp, wlp, presrc, predst, e);
         const unsigned e = len4 + tid;
-        if (e < len) ssd_glu_elems<PRE, 1>(a.h, gp, wlp, presrc, predst, e);
+        if (e < len) ssd_glu_elems<PRE, 1>(h, gp, wlp, presrc, predst, e);
     } else {
         for (unsigned e = tid; e < len; e += SSD_BLOCK)
-            ssd_glu_elems<PRE, 1>(a.h, gp, wlp, presrc, predst, e);
+            ssd_glu_elems<PRE, 1>(h, gp, wlp, presrc, predst, e);
     }
 }
 

@@ -8,7 +8,7 @@
 //     S = g_0; S = S + g_i (i = 1..K-1); gh = S*rescale; t1 = wd*w;
 //     t2 = gh + t1; t3 = lr*t2; t4 = m*mom; mom' = t4 - t3; w' = w + mom'
 //   GLU (Eq. (glu-update), grad_sync of Sec. 3.3, descent sign):
-//     q = pre_scale*pre; e = q - wl; gs = e*c_sync; u1 = alpha*g; u2 = wd_loc*wl; u3 = u1 + u2;
+//     q = pre (or pre_scale*pre, exact-w_minus variant); e = q - wl; gs = e*c_sync; u1 = alpha*g; u2 = wd_loc*wl; u3 = u1 + u2;
 //     u4 = beta*gs; u5 = u3 + u4; u6 = lr_loc*u5; wl' = wl - u6
 #pragma once
 #include <hip/hip_runtime.h>
@@ -86,15 +86,35 @@ struct ssd_hyper {
     float pre_scale;                             // 1, or 1 - lr*wd for the exact w_minus
 };
 
+// Per-tensor hyper-parameters: the global values times the tensor's learning-
+// rate and weight-decay multipliers (formed on the host), and the two derived
+// constants of grad_sync.  One 24-byte record per tensor.
+struct ssd_tensor_hyper {
+    float lr, wd, c_sync, lr_loc, wd_loc, pre_scale;
+};
+
+static __device__ __forceinline__ ssd_hyper ssd_hyper_of(const ssd_hyper &global, const ssd_tensor_hyper &t)
+{
+    ssd_hyper h = global; // rescale, m, alpha, beta are the same for all tensors
+    h.lr = t.lr;
+    h.wd = t.wd;
+    h.c_sync = t.c_sync;
+    h.lr_loc = t.lr_loc;
+    h.wd_loc = t.wd_loc;
+    h.pre_scale = t.pre_scale;
+    return h;
+}
+
 struct ssd_fused_args {
     ssd_tables tab;
     // [T][K+3] 8-byte words per tensor: weight pointer, first_block, numel,
     // then the K gradient pointers -- everything a wave needs about the
     // caller's arrays in one contiguous record
     const int64_t *rec;
+    const ssd_tensor_hyper *thyper; // [T]
     float *mom, *pre, *wl;
     int64_t A;                // elements per state array (worker stride)
-    ssd_hyper h;
+    ssd_hyper h;              // per-tensor fields are replaced from thyper
 };
 
 // Streaming kernels with dozens of concurrent read and write streams reach
@@ -114,7 +134,8 @@ struct ssd_glu_args {
     const float *pre_src;     // pre_weight array to read
     float *pre_dst;           // pre_weight array to write (init / refresh)
     float *wl;                // this worker's w'
-    ssd_hyper h;
+    const ssd_tensor_hyper *thyper; // [T]
+    ssd_hyper h;              // per-tensor fields are replaced from thyper
 };
 
 struct ssd_pull_args {
@@ -148,9 +169,14 @@ __device__ __forceinline__ void ssd_server_elem(float S, float w, float mom, con
     w_new = w + mo;
 }
 
+// XW: grad_sync from the exact w_minus of Sec. 3.2.1, (1 - lr*wd)*pre - wl.
+// pre_scale = 1 would give the same bits as XW = false, but the multiply sits
+// on the critical path of a wave and costs 1.4 % of the fused kernel's
+// throughput, so the default form is compiled without it.
+template <bool XW>
 __device__ __forceinline__ float ssd_glu_elem(float g, float wl, float pre, const ssd_hyper &h)
 {
-    float q = h.pre_scale * pre;
+    float q = XW ? h.pre_scale * pre : pre;
     float e = q - wl;
     float gs = e * h.c_sync;
     float u1 = h.alpha * g;
@@ -233,10 +259,11 @@ static inline bool ssd_aligned16_host(const void *p)
 hipError_t ssd_launch_glu(int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a);
 hipError_t ssd_launch_pull(int init, unsigned nchunks, hipStream_t s, const ssd_pull_args &a);
 hipError_t ssd_launch_fill_zero(float *p, int64_t n, hipStream_t s);
-typedef hipError_t (*ssd_fused_launcher)(int stage, int pre_action, int from_global, int waves_per_cu,
+typedef hipError_t (*ssd_fused_launcher)(int stage, int pre_action, int from_global, int exact_w_minus,
+                                         int waves_per_cu,
                                          unsigned nchunks, hipStream_t s, const ssd_fused_args &a);
 #define SSD_DECL_FUSED(k) \
-    hipError_t ssd_launch_fused_k##k(int, int, int, int, unsigned, hipStream_t, const ssd_fused_args &);
+    hipError_t ssd_launch_fused_k##k(int, int, int, int, int, unsigned, hipStream_t, const ssd_fused_args &);
 SSD_DECL_FUSED(1) SSD_DECL_FUSED(2) SSD_DECL_FUSED(3) SSD_DECL_FUSED(4)
 SSD_DECL_FUSED(5) SSD_DECL_FUSED(6) SSD_DECL_FUSED(7) SSD_DECL_FUSED(8)
 SSD_DECL_FUSED(9) SSD_DECL_FUSED(10) SSD_DECL_FUSED(11) SSD_DECL_FUSED(12)

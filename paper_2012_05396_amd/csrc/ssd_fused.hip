@@ -45,9 +45,10 @@ __device__ __forceinline__ void ssd_load_state(const ssd_fused_args &a, gfloat *
     }
 }
 
-template <int K, int STAGE, int PRE, bool FG, int VW>
-__device__ __forceinline__ void ssd_finish(const ssd_fused_args &a, cgfloat *const (&gp)[K], gfloat *wp,
-                                           gfloat *momp, gfloat *prep, gfloat *wlp, unsigned e,
+template <int K, int STAGE, int PRE, bool FG, bool XW, int VW>
+__device__ __forceinline__ void ssd_finish(const ssd_fused_args &a, const ssd_hyper &h,
+                                           cgfloat *const (&gp)[K], gfloat *wp, gfloat *momp,
+                                           gfloat *prep, gfloat *wlp, unsigned e,
                                            const ssd_state_regs<K, VW> &s)
 {
     typedef ssd_vec<VW> V;
@@ -62,7 +63,7 @@ __device__ __forceinline__ void ssd_finish(const ssd_fused_args &a, cgfloat *con
         float S = g[0][v];
 #pragma unroll
         for (int i = 1; i < K; ++i) S = S + g[i][v];
-        ssd_server_elem(S, w[v], s.mo[v], a.h, wn[v], mn[v]);
+        ssd_server_elem(S, w[v], s.mo[v], h, wn[v], mn[v]);
     }
     V::st(momp + e, mn);
     V::st(wp + e, wn);
@@ -80,7 +81,7 @@ __device__ __forceinline__ void ssd_finish(const ssd_fused_args &a, cgfloat *con
             for (int v = 0; v < VW; ++v) {
                 const float wli = FG ? w[v] : s.wl[i][v];
                 const float pv = (PRE == SSD_PRE_INIT) ? wli : s.p[v];
-                r[v] = ssd_glu_elem(g[i][v], wli, pv, a.h);
+                r[v] = ssd_glu_elem<XW>(g[i][v], wli, pv, h);
             }
             V::st(wlp + i * a.A + e, r);
         }
@@ -91,13 +92,14 @@ __device__ __forceinline__ void ssd_finish(const ssd_fused_args &a, cgfloat *con
 // Full vectors take the 128-bit path; a lane at the ragged end of the block,
 // or any lane when a caller pointer is not 16-byte aligned, goes element by
 // element -- in both cases with the state values preloaded in `s`.
-template <int K, int STAGE, int PRE, bool FG>
-__device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, cgfloat *const (&gp)[K], gfloat *wp,
-                                         gfloat *momp, gfloat *prep, gfloat *wlp, unsigned e0,
-                                         unsigned len, bool vec, const ssd_state_regs<K, 4> &s)
+template <int K, int STAGE, int PRE, bool FG, bool XW>
+__device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, const ssd_hyper &h,
+                                         cgfloat *const (&gp)[K], gfloat *wp, gfloat *momp,
+                                         gfloat *prep, gfloat *wlp, unsigned e0, unsigned len, bool vec,
+                                         const ssd_state_regs<K, 4> &s)
 {
     if (vec && e0 + 3 < len) {
-        ssd_finish<K, STAGE, PRE, FG, 4>(a, gp, wp, momp, prep, wlp, e0, s);
+        ssd_finish<K, STAGE, PRE, FG, XW, 4>(a, h, gp, wp, momp, prep, wlp, e0, s);
     } else if (e0 < len) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -107,7 +109,7 @@ __device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, cgfloat *const
                 s1.p[0] = s.p[v];
 #pragma unroll
                 for (int i = 0; i < K; ++i) s1.wl[i][0] = s.wl[i][v];
-                ssd_finish<K, STAGE, PRE, FG, 1>(a, gp, wp, momp, prep, wlp, e0 + v, s1);
+                ssd_finish<K, STAGE, PRE, FG, XW, 1>(a, h, gp, wp, momp, prep, wlp, e0 + v, s1);
             }
         }
     }
@@ -116,11 +118,13 @@ __device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, cgfloat *const
 // The arguments a wave needs first come as separate leading kernel arguments
 // so that they can be preloaded into scalar registers at wave launch
 // (-amdgpu-kernarg-preload-count); the rest arrives with ordinary scalar loads.
-template <int K, int STAGE, int PRE, bool FG>
+template <int K, int STAGE, int PRE, bool FG, bool XW>
 __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *block_tensor, float *mom,
                                                               float *pre, float *wl, int64_t A,
                                                               unsigned C, unsigned blocks_per_xcd,
-                                                              const int64_t *rec_table, const ssd_hyper h)
+                                                              const int64_t *rec_table,
+                                                              const ssd_tensor_hyper *thyper,
+                                                              const ssd_hyper hglobal)
 {
     ssd_fused_args a;
     a.tab.block_tensor = block_tensor;
@@ -132,7 +136,8 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
     a.pre = pre;
     a.wl = wl;
     a.A = A;
-    a.h = h;
+    a.thyper = thyper;
+    a.h = hglobal;
     const unsigned lane = threadIdx.x;
     // head of the lookup chain: request it first
     const int t = a.tab.block_tensor[ssd_block_slot(blockIdx.x, a.tab.blocks_per_xcd)];
@@ -145,6 +150,8 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
     ssd_load_state<K, STAGE, PRE, FG, 4>(a, momp, prep, wlp, lane * 4, s);
 
     // block -> tensor -> one record {w, first_block, numel, g_0 .. g_{K-1}}
+    // and the tensor's hyper-parameters
+    const ssd_hyper h = ssd_hyper_of(a.h, a.thyper[t]);
     const int64_t *rec = a.rec + (int64_t)t * (K + 3);
     float *w = reinterpret_cast<float *>(rec[0]);
     const int64_t off = ((int64_t)blockIdx.x - rec[1]) * a.tab.C;
@@ -162,7 +169,7 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
 
     unsigned base = 0;
     for (;;) {
-        ssd_tile<K, STAGE, PRE, FG>(a, gp, wp, momp, prep, wlp, base + lane * 4, len, vec, s);
+        ssd_tile<K, STAGE, PRE, FG, XW>(a, h, gp, wp, momp, prep, wlp, base + lane * 4, len, vec, s);
         base += SSD_BLOCK * 4;
         if (base >= len) break; // uniform
         ssd_load_state<K, STAGE, PRE, FG, 4>(a, momp, prep, wlp, base + lane * 4, s);
@@ -172,27 +179,34 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
 #define SSD_CAT2(a, b) a##b
 #define SSD_CAT(a, b) SSD_CAT2(a, b)
 
-hipError_t SSD_CAT(ssd_launch_fused_k, SSD_K)(int stage, int pre_action, int from_global, int waves_per_cu, unsigned nchunks,
-                                               hipStream_t s, const ssd_fused_args &a)
+hipError_t SSD_CAT(ssd_launch_fused_k, SSD_K)(int stage, int pre_action, int from_global, int exact_w_minus,
+                                               int waves_per_cu, unsigned nchunks, hipStream_t s,
+                                               const ssd_fused_args &a)
 {
     const dim3 grid(nchunks), block(SSD_BLOCK);
     const unsigned lds = ssd_lds_for_waves(waves_per_cu); // occupancy cap only, never accessed
-#define SSD_GO(ST, PR, FG)                                                         \
+#define SSD_GO(ST, PR, FG, XW)                                                     \
     do {                                                                           \
         if (lds > 65536)                                                           \
-            (void)hipFuncSetAttribute((const void *)ssd_fused_kernel<SSD_K, ST, PR, FG>,   \
+            (void)hipFuncSetAttribute((const void *)ssd_fused_kernel<SSD_K, ST, PR, FG, XW>, \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        ssd_fused_kernel<SSD_K, ST, PR, FG><<<grid, block, lds, s>>>(                \
-            a.tab.block_tensor, a.mom, a.pre, a.wl, a.A, a.tab.C, a.tab.blocks_per_xcd, a.rec, a.h); \
+        ssd_fused_kernel<SSD_K, ST, PR, FG, XW><<<grid, block, lds, s>>>(            \
+            a.tab.block_tensor, a.mom, a.pre, a.wl, a.A, a.tab.C, a.tab.blocks_per_xcd, a.rec, a.thyper,  \
+            a.h);                                                                    \
         return hipGetLastError();                                                  \
     } while (0)
-    if (stage == SSD_STAGE_WARMUP) SSD_GO(SSD_STAGE_WARMUP, SSD_PRE_KEEP, false);
+#define SSD_GO_DELAY(PR, FG)                                                       \
+    do {                                                                           \
+        if (exact_w_minus) SSD_GO(SSD_STAGE_DELAY, PR, FG, true);                  \
+        SSD_GO(SSD_STAGE_DELAY, PR, FG, false);                                    \
+    } while (0)
+    if (stage == SSD_STAGE_WARMUP) SSD_GO(SSD_STAGE_WARMUP, SSD_PRE_KEEP, false, false);
     if (stage == SSD_STAGE_DELAY) {
-        if (pre_action == SSD_PRE_KEEP && !from_global) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_KEEP, false);
-        if (pre_action == SSD_PRE_INIT && !from_global) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_INIT, false);
-        if (pre_action == SSD_PRE_INIT && from_global) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_INIT, true);
-        if (pre_action == SSD_PRE_REFRESH && !from_global) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_REFRESH, false);
-        if (pre_action == SSD_PRE_REFRESH && from_global) SSD_GO(SSD_STAGE_DELAY, SSD_PRE_REFRESH, true);
+        if (pre_action == SSD_PRE_KEEP && !from_global) SSD_GO_DELAY(SSD_PRE_KEEP, false);
+        if (pre_action == SSD_PRE_INIT && !from_global) SSD_GO_DELAY(SSD_PRE_INIT, false);
+        if (pre_action == SSD_PRE_INIT && from_global) SSD_GO_DELAY(SSD_PRE_INIT, true);
+        if (pre_action == SSD_PRE_REFRESH && !from_global) SSD_GO_DELAY(SSD_PRE_REFRESH, false);
+        if (pre_action == SSD_PRE_REFRESH && from_global) SSD_GO_DELAY(SSD_PRE_REFRESH, true);
     }
     return hipErrorInvalidValue;
 }

@@ -154,7 +154,7 @@ struct Layout {
     int32_t chunk_elems = 0;
     int64_t num_chunks = 0, blocks_per_xcd = 0;
     size_t off_mom = 0, off_pre0 = 0, off_pre1 = 0, off_wl = 0, off_wloc = 0;
-    size_t off_chunks = 0, off_tensors = 0, off_gtab = 0, off_grow = 0;
+    size_t off_chunks = 0, off_tensors = 0, off_thyper = 0, off_gtab = 0, off_grow = 0;
     int row_slots = 0;
     size_t total = 0;
 };
@@ -220,6 +220,7 @@ int make_layout(const ssd_config *c, Layout *L)
     L->blocks_per_xcd = (L->num_chunks + SSD_XCDS - 1) / SSD_XCDS;
     L->off_chunks = o, o += round_up(sizeof(int32_t) * (size_t)L->blocks_per_xcd * SSD_XCDS, kWsAlign);
     L->off_tensors = o, o += round_up(sizeof(ssd_tensor_desc) * (size_t)T, kWsAlign);
+    L->off_thyper = o, o += round_up(sizeof(ssd_tensor_hyper) * (size_t)T, kWsAlign);
     L->off_gtab = o, o += round_up(sizeof(int64_t) * (size_t)T * (K + 3), kWsAlign) * kFusedSlots;
     L->row_slots = std::max(8, 2 * K);
     L->off_grow = o, o += round_up(sizeof(float *) * (size_t)T, kWsAlign) * L->row_slots;
@@ -240,6 +241,13 @@ struct ssd_ctx {
     ssd_tensor_desc *d_tensors = nullptr;
     PtrCache gtab, grow;
     ssd_hyper h;
+    // per-tensor learning-rate / weight-decay multipliers and the table of
+    // per-tensor hyper-parameters derived from them (device copy + two pinned
+    // staging copies used in turn)
+    std::vector<float> lr_mult, wd_mult;
+    ssd_tensor_hyper *d_thyper = nullptr, *h_thyper[2] = {nullptr, nullptr};
+    hipEvent_t thyper_ev[2] = {nullptr, nullptr};
+    int thyper_next = 0;
     int64_t it = 0;
     std::vector<int64_t> loc_update;
     std::vector<char> has_local, wloc_fresh;
@@ -274,6 +282,38 @@ struct ssd_ctx {
         h.pre_scale = cfg.grad_sync_exact ? (float)(1.0 - (double)h.lr * (double)h.wd) : 1.0f;
     }
     ssd_tables tables() const { return ssd_tables{d_block_tensor, d_tensors, (unsigned)L.chunk_elems, (unsigned)L.blocks_per_xcd}; }
+    // Hyper-parameters of tensor t: global values times its multipliers, each
+    // product one binary32 multiplication; the constants of grad_sync formed
+    // from them in binary64.  A tensor with learning rate 0 is frozen on the
+    // server, so no global gradient can be inferred for it: c_sync = 0.
+    ssd_tensor_hyper tensor_hyper(int t) const
+    {
+        ssd_tensor_hyper th;
+        th.lr = h.lr * lr_mult[t];
+        th.wd = h.wd * wd_mult[t];
+        th.lr_loc = h.lr_loc * lr_mult[t];
+        th.wd_loc = h.wd_loc * wd_mult[t];
+        th.c_sync = (cfg.delay_k > 0 && th.lr != 0.0f)
+                        ? (float)((1.0 - (double)h.m) / ((double)th.lr * (double)cfg.delay_k))
+                        : 0.0f;
+        th.pre_scale = cfg.grad_sync_exact ? (float)(1.0 - (double)th.lr * (double)th.wd) : 1.0f;
+        return th;
+    }
+    // Rebuild the table and enqueue its upload on the current stream (ordered
+    // after the launches already enqueued there, before the ones to come).
+    hipError_t upload_tensor_hyper()
+    {
+        const int slot = thyper_next;
+        thyper_next ^= 1;
+        hipError_t e = hipEventSynchronize(thyper_ev[slot]); // its previous upload has run
+        if (e != hipSuccess) return e;
+        const int T = cfg.num_tensors;
+        for (int t = 0; t < T; ++t) h_thyper[slot][t] = tensor_hyper(t);
+        e = hipMemcpyAsync(d_thyper, h_thyper[slot], sizeof(ssd_tensor_hyper) * (size_t)T,
+                           hipMemcpyHostToDevice, stream);
+        if (e != hipSuccess) return e;
+        return hipEventRecord(thyper_ev[slot], stream);
+    }
     float *arr(float *base, int i) const { return base + (int64_t)i * stride_elems(); }
     int64_t stride_elems() const { return L.stride; }
 };
@@ -333,6 +373,10 @@ void ssd_destroy(ssd_ctx *ctx)
         DeviceGuard g(ctx->cfg.device);
         ctx->gtab.destroy();
         ctx->grow.destroy();
+        for (int i = 0; i < 2; ++i) {
+            if (ctx->thyper_ev[i]) (void)hipEventDestroy(ctx->thyper_ev[i]);
+            if (ctx->h_thyper[i]) (void)hipHostFree(ctx->h_thyper[i]);
+        }
     }
     delete ctx;
 }
@@ -394,6 +438,8 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
     c->loc_update.assign(K, 0);
     c->has_local.assign(K, 0);
     c->wloc_fresh.assign(K, 0);
+    c->lr_mult.assign(T, 1.0f);
+    c->wd_mult.assign(T, 1.0f);
     c->scratch.resize((size_t)T * (K + 3));
     for (int t = 0; t < T; ++t) {
         c->scratch[(size_t)t * (K + 3) + 0] = (int64_t) reinterpret_cast<uintptr_t>(weights[t]);
@@ -421,6 +467,13 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
     // slots of the caches are packed at len pointers; the workspace reserves a
     // rounded-up stride per slot, which is at least that
     SSD_INIT_HIP(c->grow.create(L.row_slots, (size_t)T, c->ws + L.off_grow), "pointer table (rows)");
+    c->d_thyper = reinterpret_cast<ssd_tensor_hyper *>(c->ws + L.off_thyper);
+    for (int i = 0; i < 2; ++i) {
+        SSD_INIT_HIP(hipHostMalloc(reinterpret_cast<void **>(&c->h_thyper[i]), sizeof(ssd_tensor_hyper) * (size_t)T,
+                                   hipHostMallocDefault), "staging for per-tensor hyper-parameters");
+        SSD_INIT_HIP(hipEventCreateWithFlags(&c->thyper_ev[i], hipEventDisableTiming), "event");
+    }
+    SSD_INIT_HIP(c->upload_tensor_hyper(), "upload per-tensor hyper-parameters");
 
     // block -> tensor table and tensor descriptors: built on the host, uploaded once
     std::vector<int32_t> block_tensor((size_t)L.blocks_per_xcd * SSD_XCDS, 0);
@@ -502,6 +555,7 @@ static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
     ssd_fused_args a;
     a.tab = c->tables();
     a.rec = rec;
+    a.thyper = c->d_thyper;
     a.mom = c->mom;
     a.pre = c->pre[c->pre_cur];
     a.wl = c->wl;
@@ -509,7 +563,8 @@ static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
     a.h = c->h;
     const int waves = c->cfg.waves_per_cu > 0 ? c->cfg.waves_per_cu
                                               : default_waves_per_cu(c->cfg.num_workers, stage, from_global);
-    e = table[c->cfg.num_workers - 1](stage, pre_action, from_global, waves, (unsigned)c->L.num_chunks, c->stream, a);
+    e = table[c->cfg.num_workers - 1](stage, pre_action, from_global, c->cfg.grad_sync_exact, waves,
+                                      (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the fused kernel");
     return SSD_OK;
 }
@@ -635,6 +690,7 @@ int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const float *const *grads_
     a.pre_src = c->pre[c->pre_cur];
     a.pre_dst = c->pre[c->pre_cur ^ 1];
     a.wl = c->arr(c->wl, worker);
+    a.thyper = c->d_thyper;
     a.h = c->h;
     e = ssd_launch_glu(pre_action, (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the GLU kernel");
@@ -669,9 +725,32 @@ int ssd_set_lr(ssd_ctx *c, float lr, float lr_loc)
 {
     if (!c) return SSD_EINVAL;
     if (c->cfg.delay_k > 0 && !(lr != 0.0f)) return c->fail(SSD_EINVAL, "lr = 0 with delay_k > 0: grad_sync divides by lr*k");
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
     c->h.lr = lr;
     c->h.lr_loc = lr_loc;
     c->set_c_sync();
+    hipError_t e = c->upload_tensor_hyper();
+    if (e != hipSuccess) return c->fail_hip(e, "upload of per-tensor hyper-parameters");
+    return SSD_OK;
+}
+
+int ssd_set_tensor_multipliers(ssd_ctx *c, const float *lr_mult, const float *wd_mult)
+{
+    if (!c) return SSD_EINVAL;
+    const int T = c->cfg.num_tensors;
+    for (int t = 0; t < T; ++t) {
+        if (lr_mult && !(lr_mult[t] >= 0.0f)) return c->fail(SSD_EINVAL, "lr_mult[%d] must be >= 0", t);
+        if (wd_mult && !(wd_mult[t] >= 0.0f)) return c->fail(SSD_EINVAL, "wd_mult[%d] must be >= 0", t);
+    }
+    DeviceGuard guard(c->cfg.device);
+    if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
+    for (int t = 0; t < T; ++t) {
+        c->lr_mult[t] = lr_mult ? lr_mult[t] : 1.0f;
+        c->wd_mult[t] = wd_mult ? wd_mult[t] : 1.0f;
+    }
+    hipError_t e = c->upload_tensor_hyper();
+    if (e != hipSuccess) return c->fail_hip(e, "upload of per-tensor hyper-parameters");
     return SSD_OK;
 }
 

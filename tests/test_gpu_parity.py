@@ -285,3 +285,73 @@ def test_two_stream_schedule_of_fig_3b():
             compare_state(ctx, m, o, exact=True, where="two streams d=%d" % d)
     ctx.ssd_set_stream(main)
     ctx.close()
+
+
+def test_per_tensor_multipliers_bit_exact():
+    """lr / wd multipliers per tensor: every tensor must follow the oracle run
+    with that tensor's own products (one binary32 multiplication each); a
+    tensor with lr_mult = 0 stays frozen on the server and on the workers'
+    side only decays by nothing (lr_loc = 0)."""
+    print("case: per-tensor multipliers", flush=True)
+    from oracle.ssd_oracle import Oracle
+    from paper_2012_05396_amd import binding as B
+    numel, K, k, W = ODD, 3, 2, 1
+    lr, m_, wd = 0.1, 0.9, 1e-3
+    lr_mult = [1.0, 0.5, 2.0, 0.0, 1.0, 0.25, 1.0, 3.0, 1.0, 0.0, 1.5, 1.0]
+    wd_mult = [1.0, 0.0, 1.0, 1.0, 0.0, 2.0, 1.0, 1.0, 0.5, 0.0, 1.0, 0.0]
+    model = Model(numel, K, seed=51)
+    ctx = B.Context(B.make_config(numel, K, k, W, lr, m_, wd, grad_sync_exact=1,
+                                  stream=torch.cuda.current_stream().cuda_stream), model.weights)
+    ctx.ssd_set_tensor_multipliers(lr_mult, wd_mult)
+    f = np.float32
+    lr_loc = f(4.0) * f(lr)
+    offs = np.concatenate([[0], np.cumsum(numel)])
+
+    def oracle_for(t, lr_now, lr_loc_now):
+        return dict(lr=float(f(lr_now) * f(lr_mult[t])), wd=float(f(wd) * f(wd_mult[t])),
+                    lr_loc=float(f(lr_loc_now) * f(lr_mult[t])), wd_loc=float(f(wd) * f(wd_mult[t])))
+
+    oracles = {}
+    for t in range(len(numel)):
+        if lr_mult[t] == 0.0:
+            continue
+        hp = oracle_for(t, lr, lr_loc)
+        oracles[t] = Oracle(model.w0[offs[t]:offs[t + 1]], K=K, k=k, W=W, lr=hp["lr"], m=m_, wd=hp["wd"],
+                            lr_loc=hp["lr_loc"], wd_loc=hp["wd_loc"], exact_w_minus=True, mode="f32")
+    for it in range(W + 3 * k + 1):
+        if it == W + 2:                    # a learning-rate change re-derives every tensor's values
+            lr, lr_loc = 0.05, f(0.15)
+            ctx.ssd_set_lr(lr, float(lr_loc))
+            for t, o in oracles.items():
+                hp = oracle_for(t, lr, lr_loc)
+                o.set_lr(hp["lr"], hp["lr_loc"])
+        p = it % 3
+        ctx.ssd_step(model.g_dev[p])
+        for t, o in oracles.items():
+            o.step([g[offs[t]:offs[t + 1]] for g in model.g_host[p]])
+        torch.cuda.synchronize()
+        v = ctx.ssd_get_state()
+        mom = ctx.state_tensors("mom")
+        for t in range(len(numel)):
+            w_t = model.weights[t].cpu().numpy()
+            if t not in oracles:           # frozen
+                assert np.array_equal(w_t, model.w0[offs[t]:offs[t + 1]]), (it, t)
+                assert not np.any(mom[t].cpu().numpy()), (it, t)
+                if v.has_local and not v.w_local_is_global:
+                    for i in range(K):
+                        wl = ctx.state_tensors("w_local", i)[t].cpu().numpy()
+                        assert np.array_equal(wl, w_t), (it, t, i)
+                continue
+            o = oracles[t]
+            assert np.array_equal(bits(w_t), bits(o.w)), (it, t, "w")
+            assert np.array_equal(bits(mom[t]), bits(o.mom)), (it, t, "mom")
+            if v.has_local and not v.w_local_is_global:
+                for i in range(K):
+                    wl = ctx.state_tensors("w_local", i)[t]
+                    assert np.array_equal(bits(wl), bits(o.wloc[i] if v.w_local_is_global else o.wl[i])), (it, t, i)
+            elif v.has_local and v.w_loc_where == B.SSD_W_LOC_IN_W_LOCAL:
+                for i in range(K):
+                    assert np.array_equal(bits(ctx.state_tensors("w_local", i)[t]), bits(o.wloc[i])), (it, t, i)
+            if o.d > 0:
+                assert np.array_equal(bits(ctx.state_tensors("pre")[t]), bits(o.pre[0])), (it, t, "pre")
+    ctx.close()

@@ -173,3 +173,9 @@ def test_workload_shapes_match_the_published_architectures():
     for name, (n, t) in exp.items():
         numel = workloads.numels(workloads.workload(name).tensors)
         assert (sum(numel), len(numel)) == (n, t)
+
+
+def test_multipliers_reject_null_context():
+    assert B.lib.ssd_set_tensor_multipliers(None, None, None) == B.SSD_EINVAL
+    assert B.lib.ssd_set_stream(None, None) == B.SSD_EINVAL
+    assert B.lib.ssd_materialize(None) == B.SSD_EINVAL
