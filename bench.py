@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # (FETCH_SIZE + WRITE_SIZE, scaled by what the same counters read on a copy of
 # known size); see profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/ssd_fused_kernel_vgg16_K8_k4.txt: 10,272,900 KiB read + 5,404,592 KiB written
-    "vgg16": 16053751398,
+    # profiles/ssd_fused_kernel_vgg16_K8_k4.txt: 10,272,927 KiB read + 5,404,592 KiB written
+    "vgg16": 16053779046,
 }
 
 
