@@ -69,7 +69,7 @@ def main():
     ap.add_argument("--no-copy-probe", action="store_true")
     ap.add_argument("--grad-skew-elems", type=int, default=0,
                     help="worker i's gradient buffer starts i*skew elements into its allocation")
-    ap.add_argument("--cpu-sample-elems", type=int, default=16 * 1024 * 1024)
+    ap.add_argument("--cpu-sample-elems", type=int, default=64 * 1024 * 1024)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a one-GPU build (K workers are K resident sets of "
@@ -273,14 +273,14 @@ def cpu_baseline(wl, N, K, k, W, wflat, gsets, offs, numel, sample_elems):
     o = Oracle(w0, K=K, k=k, W=W, lr=wl.lr, m=wl.momentum, wd=wl.wd, mode="f32")
     for it in range(W):
         o.step(gh[it % len(gh)])
-    steps = 2 * max(k, 1)
+    steps = 4 * max(k, 1)
     t0 = time.perf_counter()
     for it in range(W, W + steps):
         o.step(gh[it % len(gh)])
     dt = (time.perf_counter() - t0) / steps
     return {"value": M / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
             "sample": "binary32 oracle (scalar C, gcc -O2 -ffp-contract=off, 1 thread) on the first "
-                      "%d elements of the same workload, %d steps-delay iterations (two k-cycles) "
+                      "%d elements of the same workload, %d steps-delay iterations (four k-cycles) "
                       "after the %d warm-up iterations" % (M, steps, W),
             "ms_per_step_on_sample": dt * 1e3, "host_cpus_visible": os.cpu_count()}
 
