@@ -76,6 +76,8 @@ struct PtrCache {
     }
     void destroy()
     {
+        for (size_t i = 0; i < ev.size(); ++i)
+            if (ev[i] && valid[i]) (void)hipEventSynchronize(ev[i]); // its upload still reads `host`
         for (hipEvent_t e : ev)
             if (e) (void)hipEventDestroy(e);
         ev.clear();
@@ -374,6 +376,7 @@ void ssd_destroy(ssd_ctx *ctx)
         ctx->gtab.destroy();
         ctx->grow.destroy();
         for (int i = 0; i < 2; ++i) {
+            if (ctx->thyper_ev[i]) (void)hipEventSynchronize(ctx->thyper_ev[i]); // staging still being read
             if (ctx->thyper_ev[i]) (void)hipEventDestroy(ctx->thyper_ev[i]);
             if (ctx->h_thyper[i]) (void)hipHostFree(ctx->h_thyper[i]);
         }
