@@ -355,3 +355,34 @@ def test_per_tensor_multipliers_bit_exact():
             if o.d > 0:
                 assert np.array_equal(bits(ctx.state_tensors("pre")[t]), bits(o.pre[0])), (it, t, "pre")
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_randomized_configurations(seed):
+    """Seeded random draws over the whole configuration space: worker count,
+    delay, warm-up length, tensor sizes (tiny, ragged, multi-block), pointer
+    misalignment, hyper-parameters, the exact-w_minus variant, chunk size."""
+    rng = np.random.default_rng(1000 + seed)
+    K = int(rng.integers(1, 17))
+    k = int(rng.integers(0, 7))
+    W = int(rng.integers(0, 4))
+    T = int(rng.integers(1, 9))
+    numel = [int(x) for x in rng.choice([1, 2, 3, 4, 5, 7, 64, 255, 256, 257, 511, 513, 1000, 1024, 1025, 3000, 5001],
+                                        size=T)]
+    hp = dict(lr=float(rng.choice([0.01, 0.1, 0.5])), momentum=float(rng.choice([0.0, 0.5, 0.9])),
+              wd=float(rng.choice([0.0, 1e-4, 1e-2])), alpha=float(rng.choice([0.0, 1.0, 2.0])),
+              beta=float(rng.choice([0.0, 0.5, 1.0])), grad_sync_exact=int(rng.integers(0, 2)))
+    if rng.random() < 0.5:
+        hp["lr_loc"] = float(rng.choice([0.05, 0.4, 1.6]))
+    if rng.random() < 0.5:
+        hp["wd_loc"] = float(rng.choice([0.0, 1e-3]))
+    if rng.random() < 0.3:
+        hp["rescale_grad"] = float(rng.choice([1.0, 0.25]))
+    w_shift = int(rng.choice([0, 0, 1, 2]))
+    g_shift = int(rng.choice([0, 0, 1, 3]))
+    chunk = int(rng.choice([0, 256, 512, 1024]))
+    steps = W + (2 * k + 2 if k else 4)
+    print("case: random seed=%d K=%d k=%d W=%d numel=%r hp=%r shifts=%d/%d chunk=%d" % (
+        seed, K, k, W, numel, hp, w_shift, g_shift, chunk), flush=True)
+    run_schedule(numel, K=K, k=k, W=W, steps=steps, hp=hp, seed=seed, w_shift=w_shift, g_shift=g_shift,
+                 chunk_elems=chunk)
