@@ -26,13 +26,16 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # (FETCH_SIZE + WRITE_SIZE, scaled by what the same counters read on a copy of
 # known size); see profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/ssd_fused_kernel_vgg16_K8_k4.txt: 10,272,927 KiB read + 5,404,592 KiB written
-    "vgg16": 16053779046,
+    # profiles/ssd_fused_kernel_vgg16_K8_k4.txt: 10,272,960 KiB read + 5,404,592 KiB written
+    ("vgg16", "f32"): 16053813047,
+    # profiles/ssd_fused_kernel_vgg16_K8_k4_bf16_gradients.txt: 8,111,157 KiB read + 5,404,592 KiB written
+    ("vgg16", "bf16"): 13840126685,
 }
 
 
-def bytes_per_element(K, kind, pre_action, from_global):
-    """fp32 bytes per model element in one iteration, as (model, moved).
+def bytes_per_element(K, kind, pre_action, from_global, gb=4):
+    """Bytes per model element in one iteration, as (model, moved); gb = bytes
+    per gradient element (4 in the benchmark configuration), all else fp32.
 
     model: what the method must move if every array of Algorithm 1 / 2 is
     kept explicitly -- reads K gradients + w + mom (+ K local weights +
@@ -43,9 +46,9 @@ def bytes_per_element(K, kind, pre_action, from_global):
     the Pull are recorded instead of copied, and the iteration after them takes
     w'_i from the global weight it loads anyway (from_global)."""
     if kind in (0, 1):
-        return (4 * K + 16 + (4 * K if kind == 1 else 0), 4 * K + 16)
-    model = 12 * K + 20 + (4 if pre_action == 2 else 0) + (4 * K if kind == 3 else 0)
-    moved = 12 * K + 20 + (4 if pre_action == 2 else 0) - (4 * K if from_global else 0)
+        return (gb * K + 16 + (4 * K if kind == 1 else 0), gb * K + 16)
+    model = (8 + gb) * K + 20 + (4 if pre_action == 2 else 0) + (4 * K if kind == 3 else 0)
+    moved = (8 + gb) * K + 20 + (4 if pre_action == 2 else 0) - (4 * K if from_global else 0)
     return (model, moved)
 
 
@@ -70,6 +73,9 @@ def main():
     ap.add_argument("--grad-skew-elems", type=int, default=0,
                     help="worker i's gradient buffer starts i*skew elements into its allocation")
     ap.add_argument("--cpu-sample-elems", type=int, default=64 * 1024 * 1024)
+    ap.add_argument("--grad-dtype", choices=["f32", "bf16", "f16"], default="f32",
+                    help="element type of the gradient buffers; 16-bit types are an extension beyond "
+                         "the paper (not the benchmark configuration)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a one-GPU build (K workers are K resident sets of "
@@ -94,14 +100,17 @@ def main():
     wflat, offs = workloads.initial_weights(wl, device=dev)
     weights = workloads.views(wflat, wl.tensors, offs)
     P = args.pool
-    gsets = [workloads.gradient_set(wl, p, device=dev, skew=args.grad_skew_elems) for p in range(P)]
+    gd = {"f32": B.SSD_GRAD_F32, "bf16": B.SSD_GRAD_BF16, "f16": B.SSD_GRAD_F16}[args.grad_dtype]
+    gb = 4 if gd == B.SSD_GRAD_F32 else 2
+    gsets = [workloads.gradient_set(wl, p, device=dev, skew=args.grad_skew_elems,
+                                    dtype=B.GRAD_TORCH_DTYPE[gd]) for p in range(P)]
     gviews = [[workloads.views(g, wl.tensors, offs) for g in gs] for gs in gsets]
     tables = [B.GradTable(g) for g in gviews]
 
     stream = torch.cuda.current_stream()
     cfg = B.make_config(numel, K, k, W, wl.lr, wl.momentum, wl.wd, device=0,
                         stream=stream.cuda_stream, chunk_elems=args.chunk_elems,
-                        waves_per_cu=args.waves_per_cu)
+                        waves_per_cu=args.waves_per_cu, grad_dtype=gd)
     ctx = B.Context(cfg, weights)
     view = ctx.ssd_get_state()
 
@@ -200,7 +209,7 @@ def main():
     for name, lst in per_kernel.items():
         ms = [x[1] for x in lst]
         key = lst[0][0]
-        moved = bytes_per_element(K, key[0] if key[0] != 3 else 2, key[1], key[2])[1]
+        moved = bytes_per_element(K, key[0] if key[0] != 3 else 2, key[1], key[2], gb)[1]
         avg = sum(ms) / len(ms)
         variants[name] = {"launches": len(ms), "avg_ms": round(avg, 4), "min_ms": round(min(ms), 4),
                           "bytes_per_elem_moved": moved,
@@ -212,21 +221,23 @@ def main():
                 "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4),
                 "algorithmic_bytes_per_launch": dom["bytes_per_elem_moved"] * N,
                 "avg_launch_ms": dom["avg_ms"],
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)}
-    model_bytes = sum(bytes_per_element(K, *q)[0] for q in kinds) * N / len(kinds)
-    moved_bytes = sum(bytes_per_element(K, *q)[1] for q in kinds) * N / len(kinds)
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.grad_dtype))}
+    model_bytes = sum(bytes_per_element(K, *q, gb)[0] for q in kinds) * N / len(kinds)
+    moved_bytes = sum(bytes_per_element(K, *q, gb)[1] for q in kinds) * N / len(kinds)
 
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(wl, N, K, k, W, wflat, gsets, offs, numel, args.cpu_sample_elems)
 
     out = {
-        "metric": "param-elements updated/s per full SSD-SGD step" + (" (UNFUSED piecewise calls)" if args.unfused else ""),
+        "metric": "param-elements updated/s per full SSD-SGD step" + (" (UNFUSED piecewise calls)" if args.unfused else "")
+                  + ("" if gb == 4 else " (EXTENSION: %s gradient buffers)" % args.grad_dtype),
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": untimed,
         "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s-shaped fp32 parameter set, N=%d elements in T=%d tensors, "
                                "K=%d workers, delay k=%d, SSGD warm-up W=%d" % (wl.name, N, T, K, k, W),
+                   "gradient_buffers": args.grad_dtype,
                    "chunk_elems": view.chunk_elems, "num_chunks": view.num_chunks,
                    "waves_per_cu": args.waves_per_cu or "library default",
                    "gradient_sets_cycled": P, "lr": wl.lr, "momentum": wl.momentum, "wd": wl.wd},
@@ -263,7 +274,7 @@ def cpu_baseline(wl, N, K, k, W, wflat, gsets, offs, numel, sample_elems):
         idx_parts.append((o, take))
         left -= take
     def gather(flat):
-        return torch.cat([flat[o:o + n] for o, n in idx_parts]).cpu().numpy()
+        return torch.cat([flat[o:o + n] for o, n in idx_parts]).to(torch.float32).cpu().numpy()
     # weights have been updated by the GPU run; any values do for timing, but
     # use fresh seeded initial weights of the same recipe for definiteness
     from paper_2012_05396_amd import workloads

@@ -10,7 +10,9 @@
  * workers are K resident sets of device arrays.
  *
  * Conventions for every entry point
- *   - All data are IEEE binary32.  Pointers named "device" point to GPU global
+ *   - All data are IEEE binary32, except that the workers' gradient buffers
+ *     may hold 16-bit values (ssd_config.grad_dtype, an extension: the paper's
+ *     gradients are binary32).  Pointers named "device" point to GPU global
  *     memory of the configured device; all other pointers are host memory
  *     that the library reads during the call only (it keeps no reference).
  *   - Calls enqueue work on the stream given at ssd_init and return without
@@ -33,8 +35,8 @@ extern "C" {
 
 #define SSD_OK 0
 #define SSD_EINVAL (-1) /* null / negative / out-of-range argument            */
-#define SSD_EALIGN (-2) /* a device pointer is not 4-byte aligned, or the
-                           workspace is not 256-byte aligned                   */
+#define SSD_EALIGN (-2) /* a device pointer is not aligned to its element
+                           size, or the workspace is not 256-byte aligned      */
 #define SSD_ENOMEM (-3) /* workspace too small, or host allocation failed     */
 #define SSD_EHIP (-4)   /* a HIP runtime call failed; text in ssd_last_error  */
 #define SSD_ESTATE (-5) /* call not allowed in the current schedule state     */
@@ -67,6 +69,19 @@ enum ssd_w_loc_where {
                                  ssd_materialize)                              */
 };
 
+/* Element type of the workers' gradient buffers.  The paper's gradients are
+ * binary32; the 16-bit types are an extension for frameworks whose backward
+ * pass emits them (mixed-precision training) and cut the bytes the update
+ * path reads.  A 16-bit gradient is widened to binary32 exactly (every
+ * bfloat16 and binary16 value is a binary32 value) as it is loaded; the
+ * arithmetic after the load is the same binary32 sequence in all three
+ * cases.  rescale_grad can carry the inverse of a loss scale. */
+enum ssd_grad_dtype {
+    SSD_GRAD_F32 = 0,  /* IEEE binary32, 4 bytes per element                   */
+    SSD_GRAD_BF16 = 1, /* bfloat16: the upper 16 bits of a binary32            */
+    SSD_GRAD_F16 = 2   /* IEEE binary16                                        */
+};
+
 typedef struct ssd_ctx ssd_ctx; /* opaque */
 
 /* Configuration.  Symbols follow Table 1 of the paper. */
@@ -97,6 +112,8 @@ typedef struct {
     int32_t grad_sync_exact; /* 0: grad_sync from (pre_weight - w') as printed
                               in Sec. 3.3; 1: from the exact w_minus of
                               Sec. 3.2.1, ((1 - lr*wd)*pre_weight - w')       */
+    int32_t grad_dtype;    /* an ssd_grad_dtype: element type of every gradient
+                              buffer passed to this context                   */
 } ssd_config;
 
 /* Device-side state, for inspection.  All arrays are "arena" arrays of
@@ -148,9 +165,10 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace,
  *   S = g_0 + g_1 + ... + g_{K-1} (in this order), g = rescale_grad * S,
  *   mom = m*mom - lr*(g + wd*w),  w = w + mom.
  *   grads  host [K] of host [T] of device pointers, read-only gradients of
- *          worker i, tensor t, numel[t] floats each.
+ *          worker i, tensor t, numel[t] elements of ssd_config.grad_dtype
+ *          each, aligned to the element size.
  * Does not advance the schedule.  (Materialises first, see ssd_materialize.) */
-int ssd_server_aggregate_update(ssd_ctx *ctx, const float *const *const *grads);
+int ssd_server_aggregate_update(ssd_ctx *ctx, const void *const *const *grads);
 
 /* One call of Algorithm 2 (GLU) for one worker, on its local weight w'_i:
  *   grad_sync = (pre_weight - w') * (1-m)/(lr*k)            (Sec. 3.3; see
@@ -163,7 +181,7 @@ int ssd_server_aggregate_update(ssd_ctx *ctx, const float *const *const *grads);
  * Needs delay_k > 0 and a worker that has pulled (SSD_ESTATE otherwise).
  * Workers must advance in lock step: a worker may be at most one local update
  * ahead of the slowest one (SSD_ESTATE otherwise); pre_weight is shared. */
-int ssd_worker_glu_update(ssd_ctx *ctx, int32_t worker, const float *const *grads_i);
+int ssd_worker_glu_update(ssd_ctx *ctx, int32_t worker, const void *const *grads_i);
 
 /* Pull of Algorithm 1 for one worker: w_loc_i = w'_i (the weights the next
  * forward/backward uses), then w'_i = w_t (current global weight).  For a
@@ -180,7 +198,7 @@ int ssd_worker_pull(ssd_ctx *ctx, int32_t worker);
  * takes it from there.  In values, equivalent bit for bit to
  * ssd_server_aggregate_update + K x ssd_worker_glu_update (+ K x
  * ssd_worker_pull).  Needs all workers at the same local update count. */
-int ssd_step(ssd_ctx *ctx, const float *const *const *grads);
+int ssd_step(ssd_ctx *ctx, const void *const *const *grads);
 
 /* Write out the state that ssd_step only records: if w_local_is_global, copy
  * the broadcast local weights into the w_loc arrays and the global weight into

@@ -15,6 +15,9 @@ SSD_MAX_WORKERS = 16
 SSD_STEP_WARMUP, SSD_STEP_WARMUP_LAST, SSD_STEP_DELAY, SSD_STEP_DELAY_PULL = 0, 1, 2, 3
 SSD_PRE_KEEP, SSD_PRE_INIT, SSD_PRE_REFRESH = 0, 1, 2
 SSD_W_LOC_IS_GLOBAL, SSD_W_LOC_IN_W_LOCAL, SSD_W_LOC_SEPARATE = 0, 1, 2
+SSD_GRAD_F32, SSD_GRAD_BF16, SSD_GRAD_F16 = 0, 1, 2
+GRAD_TORCH_DTYPE = {SSD_GRAD_F32: torch.float32, SSD_GRAD_BF16: torch.bfloat16,
+                    SSD_GRAD_F16: torch.float16}
 
 
 class ssd_config(C.Structure):
@@ -28,7 +31,7 @@ class ssd_config(C.Structure):
                 ("numel", C.POINTER(C.c_int64)),
                 ("device", C.c_int32), ("stream", C.c_void_p),
                 ("chunk_elems", C.c_int32), ("waves_per_cu", C.c_int32),
-                ("grad_sync_exact", C.c_int32)]
+                ("grad_sync_exact", C.c_int32), ("grad_dtype", C.c_int32)]
 
 
 class ssd_state_view(C.Structure):
@@ -123,7 +126,7 @@ def ssd_probe_copy(src, dst, stream=None):
 
 def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=2.0, beta=0.5, wd_loc=None,
                 rescale_grad=None, device=0, stream=None, chunk_elems=0, waves_per_cu=0,
-                grad_sync_exact=0):
+                grad_sync_exact=0, grad_dtype=SSD_GRAD_F32):
     """ssd_config with the defaults of Sec. 4.1 of the paper (loc_lr = 4*lr,
     alpha = 2, beta = 0.5) and the averaged gradient (1/K).  Returns the
     struct; it keeps the numel array alive."""
@@ -137,7 +140,7 @@ def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=2.0, beta=0
         rescale_grad=float(np.float32(1.0 / max(K, 1))) if rescale_grad is None else rescale_grad,
         num_tensors=T, numel=arr, device=device,
         stream=stream, chunk_elems=chunk_elems, waves_per_cu=waves_per_cu,
-        grad_sync_exact=grad_sync_exact)
+        grad_sync_exact=grad_sync_exact, grad_dtype=grad_dtype)
     cfg._keep = arr
     return cfg
 
@@ -192,15 +195,36 @@ class Context:
         except Exception:
             pass
 
-    @staticmethod
-    def _table(grads):
-        return grads if isinstance(grads, GradTable) else GradTable(grads)
+    def _check_row(self, row):
+        """The library sees raw pointers only: a buffer of the wrong element
+        type or size would be read out of bounds, so refuse it here."""
+        want = GRAD_TORCH_DTYPE[self.cfg.grad_dtype]
+        if len(row) != self.T:
+            raise SsdError(SSD_EINVAL, "%d gradient tensors given, %d expected" % (len(row), self.T))
+        for t, g in enumerate(row):
+            if not (g.is_cuda and g.dtype == want and g.is_contiguous() and g.numel() == self.numel[t]):
+                raise SsdError(SSD_EINVAL, "gradient tensor %d must be a contiguous %s device tensor of "
+                               "%d elements" % (t, want, self.numel[t]))
+
+    def _table(self, grads):
+        if isinstance(grads, GradTable):
+            if getattr(grads, "_checked_for", None) is not self:
+                if len(grads.tensors) != self.K:
+                    raise SsdError(SSD_EINVAL, "%d workers' gradients given, %d expected"
+                                   % (len(grads.tensors), self.K))
+                for row in grads.tensors:
+                    self._check_row(row)
+                grads._checked_for = self
+            return grads
+        g = GradTable(grads)
+        return self._table(g)
 
     def ssd_server_aggregate_update(self, grads):
         g = self._table(grads)
         _check(lib.ssd_server_aggregate_update(self.h, g.table), self.h)
 
     def ssd_worker_glu_update(self, worker, grads_i):
+        self._check_row(grads_i)
         row = (C.c_void_p * len(grads_i))(*[t.data_ptr() for t in grads_i])
         _check(lib.ssd_worker_glu_update(self.h, worker, row), self.h)
 

@@ -1,7 +1,8 @@
 """Build libssd.so (HIP, gfx950 only) in-tree with hipcc.
 
-The fused kernel is compiled once per worker count K = 1..16 so that its
-worker loops unroll; the objects are built in parallel and linked into one
+The fused kernel is compiled once per worker count K = 1..16 (so that its
+worker loops unroll) and per element type of the gradient buffers; the
+objects are built in parallel and linked into one
 shared library next to this file.
 """
 import os
@@ -14,6 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libssd.so")
 MAX_K = 16
+GRAD_DTYPES = 3  # binary32, bfloat16, binary16 gradient buffers
 
 # -ffp-contract=off: one rounding per written operation (the rounding sequence
 # is part of the library's contract).  Packed FP32 instructions stay off.
@@ -43,10 +45,11 @@ def build(jobs=None, verbose=False, defines=(), lib=None, obj_dir=None):
     os.makedirs(OBJ, exist_ok=True)
     jobs = jobs or min(8, os.cpu_count() or 1)
     units = []
-    for k in range(1, MAX_K + 1):
-        units.append((os.path.join(CSRC, "ssd_fused.hip"),
-                      os.path.join(OBJ, "ssd_fused_k%d.o" % k),
-                      ["-DSSD_K=%d" % k]))
+    for gd in range(GRAD_DTYPES):
+        for k in range(1, MAX_K + 1):
+            units.append((os.path.join(CSRC, "ssd_fused.hip"),
+                          os.path.join(OBJ, "ssd_fused_g%d_k%d.o" % (gd, k)),
+                          ["-DSSD_K=%d" % k, "-DSSD_GD=%d" % gd]))
     units.append((os.path.join(CSRC, "ssd_aux.hip"),
                   os.path.join(OBJ, "ssd_aux.o"), []))
     units.append((os.path.join(CSRC, "ssd_host.hip"),

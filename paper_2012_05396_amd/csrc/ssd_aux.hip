@@ -4,13 +4,13 @@
 // calls gives the bits of the fused step.
 #include "ssd_device.h"
 
-template <int PRE, int VW>
-__device__ __forceinline__ void ssd_glu_elems(const ssd_hyper &h, cgfloat *gp, gfloat *wlp,
+template <int PRE, int GD, int VW>
+__device__ __forceinline__ void ssd_glu_elems(const ssd_hyper &h, typename ssd_gvec<GD, 4>::ptr gp, gfloat *wlp,
                                               cgfloat *presrc, gfloat *predst, unsigned e)
 {
     typedef ssd_vec<VW> V;
     float g[VW], wl[VW], p[VW], r[VW];
-    V::ld(gp + e, g);
+    ssd_gvec<GD, VW>::ld(gp + e, g);
     V::ld(wlp + e, wl);
     if (PRE != SSD_PRE_INIT) V::ld(presrc + e, p);
 #pragma unroll
@@ -22,14 +22,15 @@ __device__ __forceinline__ void ssd_glu_elems(const ssd_hyper &h, cgfloat *gp, g
     V::st(wlp + e, r);
 }
 
-template <int PRE>
+template <int PRE, int GD>
 __global__ __launch_bounds__(SSD_BLOCK) void ssd_glu_kernel(const ssd_glu_args a)
 {
     ssd_tensor_desc td;
     const ssd_block blk = ssd_locate(a.tab, blockIdx.x, td);
-    const float *g = a.gptr[blk.tensor];
-    const bool vec = ssd_aligned16(g);
-    cgfloat *gp = ssd_global(g) + blk.off;
+    const void *g = a.gptr[blk.tensor];
+    const bool vec = ssd_grad_aligned<GD>(g);
+    typedef typename ssd_gvec<GD, 4>::ptr gptr;
+    const gptr gp = (gptr)g + blk.off;
     gfloat *wlp = ssd_global(a.wl) + blk.ao;
     cgfloat *presrc = ssd_global(a.pre_src) + blk.ao;
     gfloat *predst = ssd_global(a.pre_dst) + blk.ao;
@@ -38,25 +39,36 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_glu_kernel(const ssd_glu_args a
     if (vec) {
         const unsigned len4 = len & ~3u;
         for (unsigned e = tid * 4; e < len4; e += SSD_BLOCK * 4)
-            ssd_glu_elems<PRE, 4>(h, gp, wlp, presrc, predst, e);
+            ssd_glu_elems<PRE, GD, 4>(h, gp, wlp, presrc, predst, e);
         const unsigned e = len4 + tid;
-        if (e < len) ssd_glu_elems<PRE, 1>(h, gp, wlp, presrc, predst, e);
+        if (e < len) ssd_glu_elems<PRE, GD, 1>(h, gp, wlp, presrc, predst, e);
     } else {
         for (unsigned e = tid; e < len; e += SSD_BLOCK)
-            ssd_glu_elems<PRE, 1>(h, gp, wlp, presrc, predst, e);
+            ssd_glu_elems<PRE, GD, 1>(h, gp, wlp, presrc, predst, e);
     }
 }
 
-hipError_t ssd_launch_glu(int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a)
+template <int GD>
+static hipError_t ssd_launch_glu_of(int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a)
 {
     const dim3 grid(nchunks), block(SSD_BLOCK);
     switch (pre_action) {
-    case SSD_PRE_KEEP: ssd_glu_kernel<SSD_PRE_KEEP><<<grid, block, 0, s>>>(a); break;
-    case SSD_PRE_INIT: ssd_glu_kernel<SSD_PRE_INIT><<<grid, block, 0, s>>>(a); break;
-    case SSD_PRE_REFRESH: ssd_glu_kernel<SSD_PRE_REFRESH><<<grid, block, 0, s>>>(a); break;
+    case SSD_PRE_KEEP: ssd_glu_kernel<SSD_PRE_KEEP, GD><<<grid, block, 0, s>>>(a); break;
+    case SSD_PRE_INIT: ssd_glu_kernel<SSD_PRE_INIT, GD><<<grid, block, 0, s>>>(a); break;
+    case SSD_PRE_REFRESH: ssd_glu_kernel<SSD_PRE_REFRESH, GD><<<grid, block, 0, s>>>(a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+hipError_t ssd_launch_glu(int grad_dtype, int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a)
+{
+    switch (grad_dtype) {
+    case SSD_GRAD_F32: return ssd_launch_glu_of<SSD_GRAD_F32>(pre_action, nchunks, s, a);
+    case SSD_GRAD_BF16: return ssd_launch_glu_of<SSD_GRAD_BF16>(pre_action, nchunks, s, a);
+    case SSD_GRAD_F16: return ssd_launch_glu_of<SSD_GRAD_F16>(pre_action, nchunks, s, a);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 // INIT: w'_i = w_t and w_loc_i = w_t.  Otherwise w_loc_i = w'_i, then w'_i = w_t.

@@ -130,7 +130,7 @@ static inline unsigned ssd_lds_for_waves(int waves_per_cu)
 
 struct ssd_glu_args {
     ssd_tables tab;
-    const float *const *gptr; // [T] gradient pointers of the one worker
+    const void *const *gptr;  // [T] gradient pointers of the one worker
     const float *pre_src;     // pre_weight array to read
     float *pre_dst;           // pre_weight array to write (init / refresh)
     float *wl;                // this worker's w'
@@ -250,20 +250,88 @@ static __device__ __forceinline__ bool ssd_aligned16(const void *p)
     return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
 }
 
+// Gradient buffers hold binary32, bfloat16 or binary16 elements (GD is an
+// ssd_grad_dtype).  A 16-bit gradient is widened to binary32 as it is loaded:
+// bfloat16 by moving its bits into the upper half of the word, binary16 by the
+// hardware conversion; both are exact, so everything after the load is the
+// same arithmetic on the same values for all three types.  Four elements are
+// one 128-bit (binary32) or one 64-bit (16-bit types) load.
+template <int GD> struct ssd_grad {
+    typedef float elem;
+};
+template <> struct ssd_grad<SSD_GRAD_BF16> {
+    typedef uint16_t elem;
+};
+template <> struct ssd_grad<SSD_GRAD_F16> {
+    typedef uint16_t elem;
+};
+
+template <int GD, int VW> struct ssd_gvec;
+template <int VW> struct ssd_gvec<SSD_GRAD_F32, VW> {
+    typedef cgfloat *ptr;
+    static __device__ __forceinline__ void ld(ptr p, float (&x)[VW]) { ssd_vec<VW>::ld(p, x); }
+};
+template <> struct ssd_gvec<SSD_GRAD_BF16, 1> {
+    typedef __attribute__((address_space(1))) const uint16_t *ptr;
+    static __device__ __forceinline__ void ld(ptr p, float (&x)[1])
+    {
+        x[0] = __uint_as_float((uint32_t)__builtin_nontemporal_load(p) << 16);
+    }
+};
+template <> struct ssd_gvec<SSD_GRAD_BF16, 4> {
+    typedef __attribute__((address_space(1))) const uint16_t *ptr;
+    typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ void ld(ptr p, float (&x)[4])
+    {
+        const u2 v = __builtin_nontemporal_load((__attribute__((address_space(1))) const u2 *)p);
+        x[0] = __uint_as_float(v.x << 16);
+        x[1] = __uint_as_float(v.x & 0xffff0000u);
+        x[2] = __uint_as_float(v.y << 16);
+        x[3] = __uint_as_float(v.y & 0xffff0000u);
+    }
+};
+template <> struct ssd_gvec<SSD_GRAD_F16, 1> {
+    typedef __attribute__((address_space(1))) const uint16_t *ptr;
+    static __device__ __forceinline__ void ld(ptr p, float (&x)[1])
+    {
+        x[0] = (float)__builtin_nontemporal_load((__attribute__((address_space(1))) const _Float16 *)p);
+    }
+};
+template <> struct ssd_gvec<SSD_GRAD_F16, 4> {
+    typedef __attribute__((address_space(1))) const uint16_t *ptr;
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ void ld(ptr p, float (&x)[4])
+    {
+        const h4 v = __builtin_nontemporal_load((__attribute__((address_space(1))) const h4 *)p);
+        x[0] = (float)v.x; x[1] = (float)v.y; x[2] = (float)v.z; x[3] = (float)v.w;
+    }
+};
+
+// the four-element path needs every pointer of the tensor aligned to one load
+template <int GD> static __device__ __forceinline__ bool ssd_grad_aligned(const void *p)
+{
+    return (reinterpret_cast<uintptr_t>(p) & (4u * sizeof(typename ssd_grad<GD>::elem) - 1u)) == 0;
+}
+
+static inline size_t ssd_grad_elem_size(int grad_dtype) { return grad_dtype == SSD_GRAD_F32 ? 4 : 2; }
+
 static inline bool ssd_aligned16_host(const void *p)
 {
     return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
 }
 
 // launchers, one translation unit each
-hipError_t ssd_launch_glu(int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a);
+hipError_t ssd_launch_glu(int grad_dtype, int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a);
 hipError_t ssd_launch_pull(int init, unsigned nchunks, hipStream_t s, const ssd_pull_args &a);
 hipError_t ssd_launch_fill_zero(float *p, int64_t n, hipStream_t s);
 typedef hipError_t (*ssd_fused_launcher)(int stage, int pre_action, int from_global, int exact_w_minus,
                                          int waves_per_cu,
                                          unsigned nchunks, hipStream_t s, const ssd_fused_args &a);
-#define SSD_DECL_FUSED(k) \
-    hipError_t ssd_launch_fused_k##k(int, int, int, int, int, unsigned, hipStream_t, const ssd_fused_args &);
+// ssd_launch_fused_g<grad_dtype>_k<K>
+#define SSD_DECL_FUSED(k)                                                                                        \
+    hipError_t ssd_launch_fused_g0_k##k(int, int, int, int, int, unsigned, hipStream_t, const ssd_fused_args &); \
+    hipError_t ssd_launch_fused_g1_k##k(int, int, int, int, int, unsigned, hipStream_t, const ssd_fused_args &); \
+    hipError_t ssd_launch_fused_g2_k##k(int, int, int, int, int, unsigned, hipStream_t, const ssd_fused_args &);
 SSD_DECL_FUSED(1) SSD_DECL_FUSED(2) SSD_DECL_FUSED(3) SSD_DECL_FUSED(4)
 SSD_DECL_FUSED(5) SSD_DECL_FUSED(6) SSD_DECL_FUSED(7) SSD_DECL_FUSED(8)
 SSD_DECL_FUSED(9) SSD_DECL_FUSED(10) SSD_DECL_FUSED(11) SSD_DECL_FUSED(12)

@@ -19,11 +19,15 @@
 // weight loads; then arithmetic and stores.  128-bit accesses whenever every
 // caller pointer of the tensor is 16-byte aligned, else element by element.
 //
-// Compiled once per K (-DSSD_K=1..16) so that the worker loops unroll.
+// Compiled once per K (-DSSD_K=1..16) so that the worker loops unroll, and per
+// element type of the gradient buffers (-DSSD_GD=0..2).
 #include "ssd_device.h"
 
 #ifndef SSD_K
 #error "compile with -DSSD_K=<number of workers>"
+#endif
+#ifndef SSD_GD
+#error "compile with -DSSD_GD=<ssd_grad_dtype of the gradient buffers>"
 #endif
 
 template <int K, int VW> struct ssd_state_regs {
@@ -45,16 +49,16 @@ __device__ __forceinline__ void ssd_load_state(const ssd_fused_args &a, gfloat *
     }
 }
 
-template <int K, int STAGE, int PRE, bool FG, bool XW, int VW>
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int VW>
 __device__ __forceinline__ void ssd_finish(const ssd_fused_args &a, const ssd_hyper &h,
-                                           cgfloat *const (&gp)[K], gfloat *wp, gfloat *momp,
+                                           const typename ssd_gvec<GD, 4>::ptr (&gp)[K], gfloat *wp, gfloat *momp,
                                            gfloat *prep, gfloat *wlp, unsigned e,
                                            const ssd_state_regs<K, VW> &s)
 {
     typedef ssd_vec<VW> V;
     float g[K][VW], w[VW];
 #pragma unroll
-    for (int i = 0; i < K; ++i) V::ld(gp[i] + e, g[i]);
+    for (int i = 0; i < K; ++i) ssd_gvec<GD, VW>::ld(gp[i] + e, g[i]);
     V::ld(wp + e, w);
 
     float wn[VW], mn[VW];
@@ -92,14 +96,14 @@ __device__ __forceinline__ void ssd_finish(const ssd_fused_args &a, const ssd_hy
 // Full vectors take the 128-bit path; a lane at the ragged end of the block,
 // or any lane when a caller pointer is not 16-byte aligned, goes element by
 // element -- in both cases with the state values preloaded in `s`.
-template <int K, int STAGE, int PRE, bool FG, bool XW>
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW>
 __device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, const ssd_hyper &h,
-                                         cgfloat *const (&gp)[K], gfloat *wp, gfloat *momp,
+                                         const typename ssd_gvec<GD, 4>::ptr (&gp)[K], gfloat *wp, gfloat *momp,
                                          gfloat *prep, gfloat *wlp, unsigned e0, unsigned len, bool vec,
                                          const ssd_state_regs<K, 4> &s)
 {
     if (vec && e0 + 3 < len) {
-        ssd_finish<K, STAGE, PRE, FG, XW, 4>(a, h, gp, wp, momp, prep, wlp, e0, s);
+        ssd_finish<K, GD, STAGE, PRE, FG, XW, 4>(a, h, gp, wp, momp, prep, wlp, e0, s);
     } else if (e0 < len) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -109,7 +113,7 @@ __device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, const ssd_hype
                 s1.p[0] = s.p[v];
 #pragma unroll
                 for (int i = 0; i < K; ++i) s1.wl[i][0] = s.wl[i][v];
-                ssd_finish<K, STAGE, PRE, FG, XW, 1>(a, h, gp, wp, momp, prep, wlp, e0 + v, s1);
+                ssd_finish<K, GD, STAGE, PRE, FG, XW, 1>(a, h, gp, wp, momp, prep, wlp, e0 + v, s1);
             }
         }
     }
@@ -118,7 +122,7 @@ __device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, const ssd_hype
 // The arguments a wave needs first come as separate leading kernel arguments
 // so that they can be preloaded into scalar registers at wave launch
 // (-amdgpu-kernarg-preload-count); the rest arrives with ordinary scalar loads.
-template <int K, int STAGE, int PRE, bool FG, bool XW>
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW>
 __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *block_tensor, float *mom,
                                                               float *pre, float *wl, int64_t A,
                                                               unsigned C, unsigned blocks_per_xcd,
@@ -157,19 +161,20 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
     const int64_t off = ((int64_t)blockIdx.x - rec[1]) * a.tab.C;
     const int64_t left = rec[2] - off;
     const unsigned len = left < (int64_t)a.tab.C ? (unsigned)left : a.tab.C;
-    cgfloat *gp[K];
+    typedef typename ssd_gvec<GD, 4>::ptr gptr;
+    gptr gp[K];
     bool vec = ssd_aligned16(w);
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-        const float *g = reinterpret_cast<const float *>(rec[3 + i]);
-        vec = vec && ssd_aligned16(g);
-        gp[i] = ssd_global(g) + off;
+        const void *g = reinterpret_cast<const void *>(rec[3 + i]);
+        vec = vec && ssd_grad_aligned<GD>(g);
+        gp[i] = (gptr)g + off;
     }
     gfloat *wp = ssd_global(w) + off;
 
     unsigned base = 0;
     for (;;) {
-        ssd_tile<K, STAGE, PRE, FG, XW>(a, h, gp, wp, momp, prep, wlp, base + lane * 4, len, vec, s);
+        ssd_tile<K, GD, STAGE, PRE, FG, XW>(a, h, gp, wp, momp, prep, wlp, base + lane * 4, len, vec, s);
         base += SSD_BLOCK * 4;
         if (base >= len) break; // uniform
         ssd_load_state<K, STAGE, PRE, FG, 4>(a, momp, prep, wlp, base + lane * 4, s);
@@ -179,7 +184,7 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
 #define SSD_CAT2(a, b) a##b
 #define SSD_CAT(a, b) SSD_CAT2(a, b)
 
-hipError_t SSD_CAT(ssd_launch_fused_k, SSD_K)(int stage, int pre_action, int from_global, int exact_w_minus,
+hipError_t SSD_CAT(SSD_CAT(SSD_CAT(ssd_launch_fused_g, SSD_GD), _k), SSD_K)(int stage, int pre_action, int from_global, int exact_w_minus,
                                                int waves_per_cu, unsigned nchunks, hipStream_t s,
                                                const ssd_fused_args &a)
 {
@@ -188,9 +193,9 @@ hipError_t SSD_CAT(ssd_launch_fused_k, SSD_K)(int stage, int pre_action, int fro
 #define SSD_GO(ST, PR, FG, XW)                                                     \
     do {                                                                           \
         if (lds > 65536)                                                           \
-            (void)hipFuncSetAttribute((const void *)ssd_fused_kernel<SSD_K, ST, PR, FG, XW>, \
+            (void)hipFuncSetAttribute((const void *)ssd_fused_kernel<SSD_K, SSD_GD, ST, PR, FG, XW>, \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        ssd_fused_kernel<SSD_K, ST, PR, FG, XW><<<grid, block, lds, s>>>(            \
+        ssd_fused_kernel<SSD_K, SSD_GD, ST, PR, FG, XW><<<grid, block, lds, s>>>(            \
             a.tab.block_tensor, a.mom, a.pre, a.wl, a.A, a.tab.C, a.tab.blocks_per_xcd, a.rec, a.thyper,  \
             a.h);                                                                    \
         return hipGetLastError();                                                  \

@@ -178,6 +178,8 @@ int check_config(const ssd_config *c)
         return fail_init(SSD_EINVAL, "chunk_elems = %d, must be 0 or a positive multiple of 256", c->chunk_elems);
     if (c->grad_sync_exact != 0 && c->grad_sync_exact != 1)
         return fail_init(SSD_EINVAL, "grad_sync_exact = %d, must be 0 or 1", c->grad_sync_exact);
+    if (c->grad_dtype != SSD_GRAD_F32 && c->grad_dtype != SSD_GRAD_BF16 && c->grad_dtype != SSD_GRAD_F16)
+        return fail_init(SSD_EINVAL, "grad_dtype = %d, must be an ssd_grad_dtype (0..2)", c->grad_dtype);
     if (c->waves_per_cu < 0) return fail_init(SSD_EINVAL, "waves_per_cu = %d, must be >= 0", c->waves_per_cu);
     if (c->device < 0) return fail_init(SSD_EINVAL, "device = %d", c->device);
     return SSD_OK;
@@ -510,17 +512,18 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
     return SSD_OK;
 }
 
-static int check_grads(ssd_ctx *c, const float *const *const *grads)
+static int check_grads(ssd_ctx *c, const void *const *const *grads)
 {
     if (!grads) return c->fail(SSD_EINVAL, "grads is NULL");
     const int T = c->cfg.num_tensors, K = c->cfg.num_workers;
+    const size_t esize = ssd_grad_elem_size(c->cfg.grad_dtype);
     for (int i = 0; i < K; ++i) {
         if (!grads[i]) return c->fail(SSD_EINVAL, "grads[%d] is NULL", i);
         for (int t = 0; t < T; ++t) {
-            const float *p = grads[i][t];
+            const void *p = grads[i][t];
             if (!p) return c->fail(SSD_EINVAL, "grads[%d][%d] is NULL", i, t);
-            if (reinterpret_cast<uintptr_t>(p) % sizeof(float))
-                return c->fail(SSD_EALIGN, "grads[%d][%d] is not 4-byte aligned", i, t);
+            if (reinterpret_cast<uintptr_t>(p) % esize)
+                return c->fail(SSD_EALIGN, "grads[%d][%d] is not %zu-byte aligned", i, t, esize);
             c->scratch[(size_t)t * (K + 3) + 3 + i] = (int64_t) reinterpret_cast<uintptr_t>(p);
         }
     }
@@ -532,7 +535,10 @@ static int check_grads(ssd_ctx *c, const float *const *const *grads)
 // element models and K = 16 on a 60 M-element one.  The best cap falls as a
 // wave carries more streams -- roughly a constant number of KiB requested per
 // compute unit -- and never goes below 4; the optimum is flat within +-1.
-static int default_waves_per_cu(int K, int stage, int from_global)
+// With 16-bit gradient buffers (sweeps at K = 1, 2, 4, 8, 16) the same caps
+// hold for the warm-up and from-global kernels; the plain kernel, whose
+// gradient loads are half as wide, takes the cap of its smaller byte count.
+static int default_waves_per_cu(int K, int stage, int from_global, bool grad16)
 {
     int loads, budget; // 128-bit loads per lane, KiB in flight per compute unit
     if (stage == SSD_STAGE_WARMUP)
@@ -540,18 +546,23 @@ static int default_waves_per_cu(int K, int stage, int from_global)
     else if (from_global)
         loads = K + 3, budget = 60;
     else
-        loads = 2 * K + 3, budget = 56;
+        loads = 2 * K + 3 - (grad16 ? K / 2 : 0), budget = 56;
     const int n = (budget + loads / 2) / loads;
     return n < 4 ? 4 : (n > 16 ? 16 : n);
 }
 
 static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
 {
-    static const ssd_fused_launcher table[SSD_MAX_WORKERS] = {
-        ssd_launch_fused_k1,  ssd_launch_fused_k2,  ssd_launch_fused_k3,  ssd_launch_fused_k4,
-        ssd_launch_fused_k5,  ssd_launch_fused_k6,  ssd_launch_fused_k7,  ssd_launch_fused_k8,
-        ssd_launch_fused_k9,  ssd_launch_fused_k10, ssd_launch_fused_k11, ssd_launch_fused_k12,
-        ssd_launch_fused_k13, ssd_launch_fused_k14, ssd_launch_fused_k15, ssd_launch_fused_k16};
+#define SSD_ROW(g)                                                                               \
+    {ssd_launch_fused_g##g##_k1,  ssd_launch_fused_g##g##_k2,  ssd_launch_fused_g##g##_k3,       \
+     ssd_launch_fused_g##g##_k4,  ssd_launch_fused_g##g##_k5,  ssd_launch_fused_g##g##_k6,       \
+     ssd_launch_fused_g##g##_k7,  ssd_launch_fused_g##g##_k8,  ssd_launch_fused_g##g##_k9,       \
+     ssd_launch_fused_g##g##_k10, ssd_launch_fused_g##g##_k11, ssd_launch_fused_g##g##_k12,      \
+     ssd_launch_fused_g##g##_k13, ssd_launch_fused_g##g##_k14, ssd_launch_fused_g##g##_k15,      \
+     ssd_launch_fused_g##g##_k16}
+    static const ssd_fused_launcher table[3][SSD_MAX_WORKERS] = {SSD_ROW(0), SSD_ROW(1), SSD_ROW(2)};
+#undef SSD_ROW
+    static_assert(SSD_GRAD_F32 == 0 && SSD_GRAD_BF16 == 1 && SSD_GRAD_F16 == 2, "rows of the launcher table");
     const int64_t *rec = nullptr;
     hipError_t e = c->gtab.get(c->scratch.data(), c->stream, &rec);
     if (e != hipSuccess) return c->fail_hip(e, "gradient pointer table");
@@ -565,8 +576,9 @@ static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
     a.A = c->stride_elems();
     a.h = c->h;
     const int waves = c->cfg.waves_per_cu > 0 ? c->cfg.waves_per_cu
-                                              : default_waves_per_cu(c->cfg.num_workers, stage, from_global);
-    e = table[c->cfg.num_workers - 1](stage, pre_action, from_global, c->cfg.grad_sync_exact, waves,
+                                              : default_waves_per_cu(c->cfg.num_workers, stage, from_global,
+                                                                     c->cfg.grad_dtype != SSD_GRAD_F32);
+    e = table[c->cfg.grad_dtype][c->cfg.num_workers - 1](stage, pre_action, from_global, c->cfg.grad_sync_exact, waves,
                                       (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the fused kernel");
     return SSD_OK;
@@ -597,7 +609,7 @@ int ssd_materialize(ssd_ctx *c)
     return materialize(c);
 }
 
-int ssd_server_aggregate_update(ssd_ctx *c, const float *const *const *grads)
+int ssd_server_aggregate_update(ssd_ctx *c, const void *const *const *grads)
 {
     if (!c) return SSD_EINVAL;
     int rc = check_grads(c, grads);
@@ -609,7 +621,7 @@ int ssd_server_aggregate_update(ssd_ctx *c, const float *const *const *grads)
     return launch_fused(c, SSD_STAGE_WARMUP, SSD_PRE_KEEP, 0);
 }
 
-int ssd_step(ssd_ctx *c, const float *const *const *grads)
+int ssd_step(ssd_ctx *c, const void *const *const *grads)
 {
     if (!c) return SSD_EINVAL;
     int rc = check_grads(c, grads);
@@ -660,16 +672,17 @@ int ssd_step(ssd_ctx *c, const float *const *const *grads)
     return SSD_OK;
 }
 
-int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const float *const *grads_i)
+int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const void *const *grads_i)
 {
     if (!c) return SSD_EINVAL;
     const int K = c->cfg.num_workers, k = c->cfg.delay_k, T = c->cfg.num_tensors;
     if (worker < 0 || worker >= K) return c->fail(SSD_EINVAL, "worker = %d, must be 0..%d", worker, K - 1);
     if (!grads_i) return c->fail(SSD_EINVAL, "grads_i is NULL");
+    const size_t esize = ssd_grad_elem_size(c->cfg.grad_dtype);
     for (int t = 0; t < T; ++t) {
         if (!grads_i[t]) return c->fail(SSD_EINVAL, "grads_i[%d] is NULL", t);
-        if (reinterpret_cast<uintptr_t>(grads_i[t]) % sizeof(float))
-            return c->fail(SSD_EALIGN, "grads_i[%d] is not 4-byte aligned", t);
+        if (reinterpret_cast<uintptr_t>(grads_i[t]) % esize)
+            return c->fail(SSD_EALIGN, "grads_i[%d] is not %zu-byte aligned", t, esize);
     }
     if (k == 0) return c->fail(SSD_ESTATE, "delay_k = 0: there is no steps-delay stage");
     if (!c->has_local[worker]) return c->fail(SSD_ESTATE, "worker %d has no local weights yet (pull first)", worker);
@@ -689,13 +702,13 @@ int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const float *const *grads_
     if (e != hipSuccess) return c->fail_hip(e, "gradient pointer table");
     ssd_glu_args a;
     a.tab = c->tables();
-    a.gptr = reinterpret_cast<const float *const *>(tab);
+    a.gptr = reinterpret_cast<const void *const *>(tab);
     a.pre_src = c->pre[c->pre_cur];
     a.pre_dst = c->pre[c->pre_cur ^ 1];
     a.wl = c->arr(c->wl, worker);
     a.thyper = c->d_thyper;
     a.h = c->h;
-    e = ssd_launch_glu(pre_action, (unsigned)c->L.num_chunks, c->stream, a);
+    e = ssd_launch_glu(c->cfg.grad_dtype, pre_action, (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the GLU kernel");
     c->loc_update[worker] = lu + 1;
     c->wloc_fresh[worker] = 0;

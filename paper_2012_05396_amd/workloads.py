@@ -192,11 +192,13 @@ def initial_weights(wl, device="cpu", align=64, shift=0):
     return flat, offs
 
 
-def gradient_set(wl, set_index, device="cpu", align=64, shift=0, skew=0):
-    """Gradients of all K workers for one iteration: a list of K flat fp32
+def gradient_set(wl, set_index, device="cpu", align=64, shift=0, skew=0, dtype=torch.float32):
+    """Gradients of all K workers for one iteration: a list of K flat
     buffers laid out like the weights.  Each tensor ~ N(0, grad_sigma),
     optionally times 1/sqrt(fan_in) per layer, optionally with a seeded
-    Bernoulli(outlier_p) mask of elements multiplied by outlier_mul."""
+    Bernoulli(outlier_p) mask of elements multiplied by outlier_mul.  Drawn
+    in fp32; a 16-bit `dtype` rounds the drawn values to that type, as a
+    mixed-precision backward pass would hand them over."""
     offs, total = layout(wl.tensors, align, shift)
     out = []
     for i in range(wl.K):
@@ -215,6 +217,11 @@ def gradient_set(wl, set_index, device="cpu", align=64, shift=0, skew=0):
                                   torch.tensor(wl.outlier_mul, device=device),
                                   torch.tensor(1.0, device=device)))
             del m
+        if dtype != torch.float32:
+            # same element offsets; keep the skew in elements of the new type
+            q = torch.empty(total + i * skew, dtype=dtype, device=device)[i * skew:]
+            q.copy_(flat)
+            flat = q
         out.append(flat)
     return out
 

@@ -110,11 +110,11 @@ int main(void)
     for (int it = 0; it < STEPS; ++it) {
         const int p = it % P;
         const float *rows[K][T];
-        const float *const *grads[K];
+        const void *const *grads[K];
         const float *og[K];
         for (int i = 0; i < K; ++i) {
             for (int t = 0; t < T; ++t) rows[i][t] = d_g[p][i][t];
-            grads[i] = rows[i];
+            grads[i] = (const void *const *)rows[i];
             og[i] = g[p][i];
         }
         SSD(ssd_step(ctx, grads));
@@ -141,7 +141,7 @@ int main(void)
         }
     }
     /* error path: a NULL gradient pointer is refused and leaves the state alone */
-    const float *const *nullgrads[K] = {NULL, NULL, NULL};
+    const void *const *nullgrads[K] = {NULL, NULL, NULL};
     if (ssd_step(ctx, nullgrads) != SSD_EINVAL) bad += 1000;
     if (v.iterations != STEPS) bad += 10000;
     ssd_destroy(ctx);

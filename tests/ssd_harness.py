@@ -18,10 +18,13 @@ def cat(tensors):
 
 class Model:
     """Weights and P sets of K gradient buffers for a list of tensor sizes,
-    on the GPU, plus flattened host copies for the oracle."""
+    on the GPU, plus flattened host copies for the oracle.  With a 16-bit
+    grad_dtype the drawn gradients are rounded to that type (torch's
+    conversion) before either side sees them: the device buffers hold the
+    16-bit values, the oracle gets the same values widened to float32."""
 
     def __init__(self, numel, K, P=3, seed=0, align=64, w_shift=0, g_shift=0, g_scale=1e-2,
-                 device="cuda"):
+                 device="cuda", grad_dtype=torch.float32):
         self.numel, self.K = list(numel), K
         rng = np.random.default_rng(seed)
 
@@ -45,9 +48,11 @@ class Model:
             hs, ds = [], []
             for i in range(K):
                 h = (rng.standard_normal(N) * g_scale).astype(np.float32)
-                flat = torch.zeros(gt, dtype=torch.float32, device=device)
+                hq = torch.from_numpy(h).to(grad_dtype)
+                h = hq.to(torch.float32).numpy()
+                flat = torch.zeros(gt, dtype=grad_dtype, device=device)
                 views = [flat[o:o + n] for o, n in zip(go, self.numel)]
-                self._scatter(views, h)
+                self._scatter(views, hq)
                 hs.append(h)
                 ds.append(views)
                 self._gflat.append(flat)
@@ -55,9 +60,11 @@ class Model:
             self.g_dev.append(ds)
 
     def _scatter(self, views, flat_host):
+        if isinstance(flat_host, np.ndarray):
+            flat_host = torch.from_numpy(flat_host)
         o = 0
         for v in views:
-            v.copy_(torch.from_numpy(flat_host[o:o + v.numel()]))
+            v.copy_(flat_host[o:o + v.numel()])
             o += v.numel()
 
 
@@ -126,14 +133,17 @@ def compare_state(ctx, model, o, exact=True, tol=1e-5, where=""):
 
 
 def run_schedule(numel, K, k, W, steps, hp=None, mode="f32", chunk_elems=256, seed=0,
-                 w_shift=0, g_shift=0, g_scale=1e-2, check_every=1, P=3, lr_changes=None):
-    """Drive ssd_step and the oracle side by side; compare after each step."""
+                 w_shift=0, g_shift=0, g_scale=1e-2, check_every=1, P=3, lr_changes=None,
+                 grad_dtype=0):
+    """Drive ssd_step and the oracle side by side; compare after each step.
+    grad_dtype: an ssd_grad_dtype value."""
     from paper_2012_05396_amd import binding as B
     hp = dict(lr=0.1, momentum=0.9, wd=1e-4) if hp is None else dict(hp)
-    model = Model(numel, K, P=P, seed=seed, w_shift=w_shift, g_shift=g_shift, g_scale=g_scale)
+    model = Model(numel, K, P=P, seed=seed, w_shift=w_shift, g_shift=g_shift, g_scale=g_scale,
+                  grad_dtype=B.GRAD_TORCH_DTYPE[grad_dtype])
     cfg = B.make_config(numel, K, k, W, device=0,
                         stream=torch.cuda.current_stream().cuda_stream,
-                        chunk_elems=chunk_elems, **hp)
+                        chunk_elems=chunk_elems, grad_dtype=grad_dtype, **hp)
     ctx = B.Context(cfg, model.weights)
     ohp = dict(lr=hp["lr"], m=hp["momentum"], wd=hp["wd"])
     for a in ("lr_loc", "alpha", "beta", "wd_loc"):

@@ -44,24 +44,27 @@ def bit_equal(a, b):
     return np.array_equal(a.view(np.int32), b.view(np.int32))
 
 
-def run_full(name, piecewise_check=False, wl=None):
+def run_full(name, piecewise_check=False, wl=None, grad_dtype=0):
+    """grad_dtype: an ssd_grad_dtype; with a 16-bit type the generator rounds
+    the drawn gradients to it and the oracle gets those values as float32."""
     from paper_2012_05396_amd import binding as B
     wl = wl or workloads.workload(name)
     dev = torch.device("cuda", 0)
     numel = workloads.numels(wl.tensors)
     T, K, k, W = len(numel), wl.K, wl.k, wl.W
     steps = W + wl.steps
-    print("case: %s N=%d T=%d K=%d k=%d steps=%d" % (name, sum(numel), T, K, k, steps), flush=True)
+    print("case: %s N=%d T=%d K=%d k=%d steps=%d grad_dtype=%d" % (name, sum(numel), T, K, k, steps, grad_dtype),
+          flush=True)
     rng = np.random.default_rng(wl.seed)
 
     wflat, offs = workloads.initial_weights(wl, device=dev)
     weights = workloads.views(wflat, wl.tensors, offs)
     P = 2
-    gsets = [workloads.gradient_set(wl, p, device=dev) for p in range(P)]
+    gsets = [workloads.gradient_set(wl, p, device=dev, dtype=B.GRAD_TORCH_DTYPE[grad_dtype]) for p in range(P)]
     gviews = [[workloads.views(g, wl.tensors, offs) for g in gs] for gs in gsets]
     tables = [B.GradTable(g) for g in gviews]
     stream = torch.cuda.current_stream().cuda_stream
-    mk = lambda: B.make_config(numel, K, k, W, wl.lr, wl.momentum, wl.wd, stream=stream)
+    mk = lambda: B.make_config(numel, K, k, W, wl.lr, wl.momentum, wl.wd, stream=stream, grad_dtype=grad_dtype)
     ctx = B.Context(mk(), weights)
     v = ctx.ssd_get_state()
     assert v.chunk_elems == 256
@@ -77,7 +80,7 @@ def run_full(name, piecewise_check=False, wl=None):
     flat_idx = torch.from_numpy(np.concatenate(flat_idx)).to(dev)
     arena_idx = torch.from_numpy(np.concatenate(arena_idx)).to(dev)
     S = flat_idx.numel()
-    take = lambda flat, idx: flat.index_select(0, idx).cpu().numpy()
+    take = lambda flat, idx: flat.index_select(0, idx).to(torch.float32).cpu().numpy()
     w0 = take(wflat, flat_idx)
     gh = [[take(g, flat_idx) for g in gs] for gs in gsets]
     oracles = [Oracle(w0, K=K, k=k, W=W, lr=wl.lr, m=wl.momentum, wd=wl.wd, mode=m)
@@ -187,6 +190,13 @@ def test_full_size_sampled_parity(name):
 @pytest.mark.parametrize("name", ["resnet56", "resnet50"])
 def test_full_size_fused_equals_piecewise_everywhere(name):
     run_full(name, piecewise_check=True)
+
+
+@pytest.mark.parametrize("name,gd", [("resnet56", 1), ("vgg16", 1), ("resnet152_k4", 1), ("vgg16", 2),
+                                     ("resnet50", 2)])
+def test_full_size_sampled_parity_16bit_gradients(name, gd):
+    """Extension beyond the paper: bfloat16 (1) / binary16 (2) gradient buffers."""
+    run_full(name, grad_dtype=gd, piecewise_check=(name == "resnet50"))
 
 
 def test_tensor_larger_than_2_to_31_elements():
