@@ -113,6 +113,7 @@ def main():
                         waves_per_cu=args.waves_per_cu, grad_dtype=gd)
     ctx = B.Context(cfg, weights)
     view = ctx.ssd_get_state()
+    props = torch.cuda.get_device_properties(dev)
 
     # untimed: the W SSGD iterations of the warm-up stage plus whole k-cycles
     untimed = max(args.warmup, W)
@@ -212,6 +213,7 @@ def main():
         moved = bytes_per_element(K, key[0] if key[0] != 3 else 2, key[1], key[2], gb)[1]
         avg = sum(ms) / len(ms)
         variants[name] = {"launches": len(ms), "avg_ms": round(avg, 4), "min_ms": round(min(ms), 4),
+                          "median_ms": round(sorted(ms)[len(ms) // 2], 4),
                           "bytes_per_elem_moved": moved,
                           "GBps": round(moved * N / (avg * 1e-3) / 1e9, 1)}
     dom_name = "delay_keep" if "delay_keep" in variants else max(variants, key=lambda q: variants[q]["launches"])
@@ -224,6 +226,29 @@ def main():
                 "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.grad_dtype))}
     model_bytes = sum(bytes_per_element(K, *q, gb)[0] for q in kinds) * N / len(kinds)
     moved_bytes = sum(bytes_per_element(K, *q, gb)[1] for q in kinds) * N / len(kinds)
+
+    # the warm-up (SSGD) iteration, reported separately: the same kernel runs
+    # for ever in a context with k = 0, here on the same weights and gradients
+    ctx.close()
+    cfg0 = B.make_config(numel, K, 0, 0, wl.lr, wl.momentum, wl.wd, device=0, stream=stream.cuda_stream,
+                         chunk_elems=args.chunk_elems, waves_per_cu=args.waves_per_cu, grad_dtype=gd)
+    ctx0 = B.Context(cfg0, weights)
+    for i in range(3):
+        ctx0.ssd_step(tables[i % P])
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+    for i in range(10):
+        ev[i].record(stream)
+        ctx0.ssd_step(tables[i % P])
+    ev[10].record(stream)
+    torch.cuda.synchronize()
+    wms = [ev[i].elapsed_time(ev[i + 1]) for i in range(10)]
+    wb = bytes_per_element(K, 0, 0, False, gb)[1]
+    wavg = sum(wms) / len(wms)
+    warmup_variant = {"launches": len(wms), "avg_ms": round(wavg, 4), "min_ms": round(min(wms), 4),
+                      "median_ms": round(sorted(wms)[len(wms) // 2], 4), "bytes_per_elem_moved": wb,
+                      "GBps": round(wb * N / (wavg * 1e-3) / 1e9, 1),
+                      "elements_per_s": N / (wavg * 1e-3)}
+    ctx0.close()
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -240,13 +265,16 @@ def main():
                    "gradient_buffers": args.grad_dtype,
                    "chunk_elems": view.chunk_elems, "num_chunks": view.num_chunks,
                    "waves_per_cu": args.waves_per_cu or "library default",
-                   "gradient_sets_cycled": P, "lr": wl.lr, "momentum": wl.momentum, "wd": wl.wd},
+                   "gradient_sets_cycled": P, "seed": wl.seed, "lr": wl.lr, "momentum": wl.momentum,
+                   "wd": wl.wd, "device": props.name, "compute_units": props.multi_processor_count,
+                   "arch": getattr(props, "gcnArchName", None)},
         "bytes_per_elem_cycle_average": {"explicit_arrays_model": round(model_bytes / N, 2),
                                          "moved": round(moved_bytes / N, 2)},
         "hbm_GBps_cycle_average_moved": round(moved_bytes / sec_per_step / 1e9, 1),
         "hbm_GBps_cycle_average_model": round(model_bytes / sec_per_step / 1e9, 1),
         "weight_elements_written_per_s": (K + 1) * value,
         "variants": variants,
+        "warmup_ssgd_iteration": warmup_variant,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "copy_probe": probe,
@@ -254,7 +282,6 @@ def main():
                    "over SSGD) are on 4 x (4 x V100, no NVLink) + 56 Gb/s InfiniBand",
     }
     print(json.dumps(out))
-    ctx.close()
 
 
 def cpu_baseline(wl, N, K, k, W, wflat, gsets, offs, numel, sample_elems):
@@ -289,7 +316,32 @@ def cpu_baseline(wl, N, K, k, W, wflat, gsets, offs, numel, sample_elems):
     for it in range(W, W + steps):
         o.step(gh[it % len(gh)])
     dt = (time.perf_counter() - t0) / steps
-    return {"value": M / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
+    del o
+    # the same oracle, unchanged, on all host cores of this process: the rules
+    # are element-wise, so C threads each run their own oracle instance on one
+    # contiguous range of the sample (the C call releases the interpreter lock)
+    from concurrent.futures import ThreadPoolExecutor
+    cores = min(16, len(os.sched_getaffinity(0)))
+    par = None
+    if cores > 1:
+        cuts = [M * j // cores for j in range(cores + 1)]
+        parts = [Oracle(w0[a:b], K=K, k=k, W=W, lr=wl.lr, m=wl.momentum, wd=wl.wd, mode="f32")
+                 for a, b in zip(cuts[:-1], cuts[1:])]
+        with ThreadPoolExecutor(cores) as ex:
+            def one_step(it):
+                gs = gh[it % len(gh)]
+                list(ex.map(lambda j: parts[j].step([g[cuts[j]:cuts[j + 1]] for g in gs]), range(cores)))
+            for it in range(W):
+                one_step(it)
+            t0 = time.perf_counter()
+            for it in range(W, W + steps):
+                one_step(it)
+            pdt = (time.perf_counter() - t0) / steps
+        par = {"value": M / pdt, "unit": "elements/s", "cores": cores, "ms_per_step_on_sample": pdt * 1e3,
+               "how": "the same oracle on %d threads, one contiguous element range each, joined after "
+                      "every iteration" % cores}
+        del parts
+    return {"value": M / dt, "unit": "elements/s", "cores": 1, "kind": "oracle", "all_cores": par,
             "sample": "binary32 oracle (scalar C, gcc -O2 -ffp-contract=off, 1 thread) on the first "
                       "%d elements of the same workload, %d steps-delay iterations (four k-cycles) "
                       "after the %d warm-up iterations" % (M, steps, W),
