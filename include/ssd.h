@@ -226,7 +226,9 @@ int ssd_set_tensor_multipliers(ssd_ctx *ctx, const float *lr_mult, const float *
  * the global weight -- must be ordered by the caller with events.  This is
  * what lets the server update and the local updates of one iteration run
  * side by side, as in the execution order of the paper's Fig. 3(b) (Push and
- * local update only read the gradient). */
+ * local update only read the gradient).  Every stream ever given to a context
+ * must stay alive until ssd_destroy: the context may have to wait for it when
+ * it reuses a pointer table that a launch on that stream has read. */
 int ssd_set_stream(ssd_ctx *ctx, void *stream);
 
 /* Fill *out (host).  Does not synchronise. */

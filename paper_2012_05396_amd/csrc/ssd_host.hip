@@ -49,7 +49,7 @@ struct PtrCache {
     std::vector<char> valid;
     std::vector<hipEvent_t> ev;
     std::vector<hipStream_t> up_stream;  // stream each slot was uploaded on
-    std::vector<hipStream_t> use_stream; // stream of the last launch that read the slot
+    std::vector<std::vector<hipStream_t>> users; // streams whose launches have read the slot
     uint64_t clock = 0;
 
     hipError_t create(int n, size_t l, void *dev_mem)
@@ -61,7 +61,7 @@ struct PtrCache {
         valid.assign(n, 0);
         ev.assign(n, nullptr);
         up_stream.assign(n, nullptr);
-        use_stream.assign(n, nullptr);
+        users.assign(n, std::vector<hipStream_t>());
         hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&host), sizeof(int64_t) * len * n,
                                      hipHostMallocDefault);
         if (e != hipSuccess) {
@@ -96,7 +96,7 @@ struct PtrCache {
                     hipError_t e = hipStreamWaitEvent(s, ev[i], 0);
                     if (e != hipSuccess) return e;
                 }
-                use_stream[i] = s;
+                if (std::find(users[i].begin(), users[i].end(), s) == users[i].end()) users[i].push_back(s);
                 return hipSuccess;
             }
         int lru = -1;
@@ -111,10 +111,11 @@ struct PtrCache {
         if (valid[lru]) {
             e = hipEventSynchronize(ev[lru]); // staging copy may still be queued
             if (e != hipSuccess) return e;
-            if (use_stream[lru] != s) { // a launch on another stream may still read the old table
-                e = hipStreamSynchronize(use_stream[lru]);
-                if (e != hipSuccess) return e;
-            }
+            for (hipStream_t u : users[lru])
+                if (u != s) { // a launch on another stream may still read the old table
+                    e = hipStreamSynchronize(u);
+                    if (e != hipSuccess) return e;
+                }
         }
         valid[lru] = 0;
         std::memcpy(host + lru * len, key, sizeof(int64_t) * len);
@@ -125,7 +126,7 @@ struct PtrCache {
         if (e != hipSuccess) return e;
         valid[lru] = 1;
         up_stream[lru] = s;
-        use_stream[lru] = s;
+        users[lru].assign(1, s);
         stamp[lru] = clock;
         *out = dev + lru * len;
         return hipSuccess;
