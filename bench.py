@@ -30,6 +30,9 @@ MEASURED_TRAFFIC_BYTES = {
     ("vgg16", "f32"): 16053813047,
     # profiles/ssd_fused_kernel_vgg16_K8_k4_bf16_gradients.txt: 8,111,157 KiB read + 5,404,592 KiB written
     ("vgg16", "bf16"): 13840126685,
+    # profiles/ssd_fused_kernel_resnet50_K8_k5.txt, profiles/ssd_fused_kernel_resnet152_K16_k4.txt
+    ("resnet50", "f32"): 2965884324,
+    ("resnet152_k4", "f32"): 12764143822,
 }
 
 
