@@ -532,24 +532,25 @@ static int check_grads(ssd_ctx *c, const void *const *const *grads)
 }
 
 // Resident waves per compute unit that gave the highest HBM throughput when
-// measured on MI355X: sweeps over 3..16 waves for K = 1, 2, 4, 8 on 133-138 M-
-// element models and K = 16 on a 60 M-element one.  The best cap falls as a
-// wave carries more streams -- roughly a constant number of KiB requested per
-// compute unit -- and never goes below 4; the optimum is flat within +-1.
-// With 16-bit gradient buffers (sweeps at K = 1, 2, 4, 8, 16) the same caps
-// hold for the warm-up and from-global kernels; the plain kernel, whose
-// gradient loads are half as wide, takes the cap of its smaller byte count.
+// measured on MI355X: sweeps over 2..16 waves for K = 1, 2, 4, 8 on 133-138 M-
+// element models and K = 16 on a 60 M-element one, with binary32 and with
+// bfloat16 gradient buffers.  The best cap falls as a wave carries more
+// streams, roughly as budget / (loads per lane), and is flat within +-1:
+//   plain delay kernel   58 / (2K + 3), at least 4   (K = 8: 4, K = 2: 8)
+//   from-global kernel   44 / (K + 3),  at least 4   (50 with 16-bit gradients)
+//   warm-up kernel       58 / (K + 2),  at least 6   (read-dominated: its
+//                        16-bit gradient loads count half, budget 52)
 static int default_waves_per_cu(int K, int stage, int from_global, bool grad16)
 {
-    int loads, budget; // 128-bit loads per lane, KiB in flight per compute unit
+    int loads2, budget, floor_n; // loads per lane in halves of a 128-bit load
     if (stage == SSD_STAGE_WARMUP)
-        loads = K + 2, budget = 80;
+        loads2 = (grad16 ? K : 2 * K) + 4, budget = grad16 ? 52 : 58, floor_n = 6;
     else if (from_global)
-        loads = K + 3, budget = 60;
+        loads2 = 2 * (K + 3), budget = grad16 ? 50 : 44, floor_n = 4;
     else
-        loads = 2 * K + 3 - (grad16 ? K / 2 : 0), budget = 56;
-    const int n = (budget + loads / 2) / loads;
-    return n < 4 ? 4 : (n > 16 ? 16 : n);
+        loads2 = 2 * (2 * K + 3), budget = 58, floor_n = 4;
+    const int n = (2 * budget + loads2 / 2) / loads2;
+    return n < floor_n ? floor_n : (n > 16 ? 16 : n);
 }
 
 static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
