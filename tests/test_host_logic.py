@@ -36,6 +36,23 @@ def test_binding_names_match_header():
         assert hasattr(B, n) or hasattr(B.Context, n), n
 
 
+def test_binding_constants_and_config_layout_match_header():
+    """Every enumerator and error code of the header has the same value in the
+    binding, and the ctypes ssd_config lists the header's fields in order."""
+    src = open(os.path.join(ROOT, "include", "ssd.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    consts = dict((n, int(v)) for n, v in re.findall(r"\b(SSD_[A-Z0-9_]+)\s*=\s*(-?\d+)", src))
+    consts.update((n, int(v)) for n, v in re.findall(r"#define\s+(SSD_[A-Z0-9_]+)\s+\(?(-?\d+)\)?", src))
+    assert len(consts) >= 20
+    for n, v in consts.items():
+        assert getattr(B, n) == v, n
+    body = re.search(r"typedef struct \{(.*?)\} ssd_config;", src, flags=re.S).group(1)
+    fields = re.findall(r"\b(\w+)\s*;", body)
+    assert fields == [f[0] for f in B.ssd_config._fields_]
+    body = re.search(r"typedef struct \{((?:(?!typedef struct).)*?)\} ssd_state_view;", src, flags=re.S).group(1)
+    assert re.findall(r"\b(\w+)\s*;", body) == [f[0] for f in B.ssd_state_view._fields_]
+
+
 # ---- schedule (Alg. 1 warm-up loop / steps-delay loop, Alg. 2 pre_weight) ----
 @pytest.mark.parametrize("wp,k", [(0, 1), (1, 2), (3, 4), (5, 3), (9, 5), (7, 8)])
 def test_step_kind_follows_algorithm_1_when_aligned(wp, k):
