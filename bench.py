@@ -76,6 +76,8 @@ def main():
     ap.add_argument("--grad-skew-elems", type=int, default=0,
                     help="worker i's gradient buffer starts i*skew elements into its allocation")
     ap.add_argument("--cpu-sample-elems", type=int, default=64 * 1024 * 1024)
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the same steps as replays of a HIP graph holding whole k-cycles")
     ap.add_argument("--grad-dtype", choices=["f32", "bf16", "f16"], default="f32",
                     help="element type of the gradient buffers; 16-bit types are an extension beyond "
                          "the paper (not the benchmark configuration)")
@@ -244,6 +246,36 @@ def main():
         bare_ms = (time.perf_counter() - tb0) / args.steps * 1e3
         it += args.steps
 
+    # optionally: whole k-cycles captured once into a HIP graph and replayed
+    graph_ms = None
+    if args.graph and not args.unfused and k > 0:
+        import math
+        side = torch.cuda.Stream()
+        ctx.ssd_set_stream(side)
+        L = k * P // math.gcd(k, P)
+        with torch.cuda.stream(side):
+            while (it - W) % k != 0:          # to a cycle boundary
+                ctx.ssd_step(tables[it % P])
+                it += 1
+            for _ in range(L):                # every table used once on this stream
+                ctx.ssd_step(tables[it % P])
+                it += 1
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side, capture_error_mode="thread_local"):
+            for j in range(L):
+                ctx.ssd_step(tables[(it + j) % P])
+        it += L
+        reps = max(1, args.steps // L)
+        g.replay()
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - tg0) / (reps * L) * 1e3
+        ctx.ssd_set_stream(stream.cuda_stream)
+
     # the warm-up (SSGD) iteration, reported separately: the same kernel runs
     # for ever in a context with k = 0, here on the same weights and gradients
     ctx.close()
@@ -276,6 +308,7 @@ def main():
                   + ("" if gb == 4 else " (EXTENSION: %s gradient buffers)" % args.grad_dtype),
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": untimed,
         "ms_per_step": sec_per_step * 1e3, "ms_per_step_uninstrumented_repeat": bare_ms,
+        "ms_per_step_graph_replay": graph_ms,
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s-shaped fp32 parameter set, N=%d elements in T=%d tensors, "

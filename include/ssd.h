@@ -197,7 +197,19 @@ int ssd_worker_pull(ssd_ctx *ctx, int32_t worker);
  * the global weight (ssd_state_view.w_local_is_global) and the next iteration
  * takes it from there.  In values, equivalent bit for bit to
  * ssd_server_aggregate_update + K x ssd_worker_glu_update (+ K x
- * ssd_worker_pull).  Needs all workers at the same local update count. */
+ * ssd_worker_pull).  Needs all workers at the same local update count.
+ *
+ * Graph capture.  Once a set of gradient pointers has been used on a stream
+ * (the context keeps the pointer tables of the last 8 distinct sets on the
+ * device), a further ssd_step with it on that stream enqueues exactly one
+ * kernel launch: no copy, no memset, no allocation, no wait.  Such calls may be
+ * recorded into a HIP graph by capturing the stream.  A graph that holds whole
+ * k-cycles starting at a cycle boundary (local_updates % k == 0, after at
+ * least one earlier cycle) can be replayed any number of times: the recorded
+ * flags return to their values at the start of the cycle, so each replay is
+ * the next k iterations.  Replays do not advance the counters that
+ * ssd_get_state reports, and the captured gradient sets must not be evicted
+ * (use at most 8 distinct sets while the graph lives). */
 int ssd_step(ssd_ctx *ctx, const void *const *const *grads);
 
 /* Write out the state that ssd_step only records: if w_local_is_global, copy

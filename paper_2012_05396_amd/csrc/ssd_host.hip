@@ -92,11 +92,16 @@ struct PtrCache {
             if (valid[i] && std::memcmp(host + i * len, key, sizeof(int64_t) * len) == 0) {
                 stamp[i] = clock;
                 *out = dev + i * len;
-                if (up_stream[i] != s) { // uploaded on another stream: order this one after it
-                    hipError_t e = hipStreamWaitEvent(s, ev[i], 0);
-                    if (e != hipSuccess) return e;
+                if (std::find(users[i].begin(), users[i].end(), s) == users[i].end()) {
+                    // first use on this stream: order it after the upload, once
+                    // (later launches on the stream follow in stream order, so a
+                    // steady-state call enqueues nothing but its kernel)
+                    if (up_stream[i] != s) {
+                        hipError_t e = hipStreamWaitEvent(s, ev[i], 0);
+                        if (e != hipSuccess) return e;
+                    }
+                    users[i].push_back(s);
                 }
-                if (std::find(users[i].begin(), users[i].end(), s) == users[i].end()) users[i].push_back(s);
                 return hipSuccess;
             }
         int lru = -1;
