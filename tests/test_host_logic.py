@@ -133,6 +133,17 @@ def test_workspace_bytes_rejects_bad_config(kw):
     assert e.value.code == B.SSD_EINVAL and len(str(e.value)) > 20
 
 
+def test_model_beyond_one_launch_is_rejected():
+    """A grid holds at most 2^31 - 1 blocks; 2^31 blocks of 256 elements must be
+    refused by the host (before any device work), a chunk size that brings the
+    count back under the limit accepted."""
+    big = 256 * 2 ** 31
+    with pytest.raises(B.SsdError) as e:
+        B.ssd_workspace_bytes(_cfg(numel=[big]))
+    assert e.value.code == B.SSD_EINVAL and "chunks" in str(e.value)
+    assert B.ssd_workspace_bytes(_cfg(numel=[big], chunk_elems=512)) > 4 * big
+
+
 def test_workspace_bytes_counts_the_state_arrays():
     # k = 0: momentum only.  k > 0: momentum, two pre_weight arrays, K local
     # weights, K w_loc; every tensor owns whole blocks of 256 elements.
