@@ -199,6 +199,14 @@ def test_full_size_sampled_parity_16bit_gradients(name, gd):
     run_full(name, grad_dtype=gd, piecewise_check=(name == "resnet50"))
 
 
+def test_long_schedule_stays_bit_exact():
+    """300 steps-delay iterations (75 Pulls) on the ResNet-56-shaped set: no
+    drift between the library and the binary32 oracle, and the binary64
+    oracle still within 1e-5."""
+    wl = workloads.workload("resnet56")._replace(steps=300)
+    run_full("resnet56-long", wl=wl)
+
+
 def test_tensor_larger_than_2_to_31_elements():
     """64-bit offsets: one tensor of 2^31 + 1029 elements (8.6 GB per array),
     sampled at its ends, around block boundaries and at random positions,
