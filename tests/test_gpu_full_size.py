@@ -199,6 +199,79 @@ def test_full_size_sampled_parity_16bit_gradients(name, gd):
     run_full(name, grad_dtype=gd, piecewise_check=(name == "resnet50"))
 
 
+@pytest.mark.parametrize("name,gd", [("vgg16", 0), ("resnet152_k4", 0), ("vgg16", 1)])
+def test_every_element_bit_exact_at_full_size(name, gd):
+    """The 138 M-element benchmark configuration (also with bfloat16 gradient
+    buffers) and the K = 16 one, every element of every array:
+    the binary32 oracle runs on all host threads (one contiguous element range
+    each -- the rules are element-wise) through warm-up, the first local
+    update, a Pull and the refresh after it, and the whole GPU state is
+    compared bit for bit at two points of the schedule."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    import psutil
+    from paper_2012_05396_amd import binding as B
+    if psutil.virtual_memory().available < 64 * 2 ** 30:
+        pytest.skip("needs 64 GB of free host memory for the oracle's copy of the model")
+    wl = workloads.workload(name)
+    dev = torch.device("cuda", 0)
+    numel = workloads.numels(wl.tensors)
+    N, K, k, W = sum(numel), wl.K, wl.k, wl.W
+    print("case: %s every element, N=%d K=%d k=%d grad_dtype=%d" % (name, N, K, k, gd), flush=True)
+    wflat, offs = workloads.initial_weights(wl, device=dev)
+    weights = workloads.views(wflat, wl.tensors, offs)
+    P = 2
+    gsets = [workloads.gradient_set(wl, p, device=dev, dtype=B.GRAD_TORCH_DTYPE[gd]) for p in range(P)]
+    gviews = [[workloads.views(g, wl.tensors, offs) for g in gs] for gs in gsets]
+    tables = [B.GradTable(g) for g in gviews]
+    host = lambda views: torch.cat([v.reshape(-1) for v in views]).to(torch.float32).cpu().numpy()
+    w0 = host(weights)
+    gh = [[host(v) for v in gs] for gs in gviews]
+    ctx = B.Context(B.make_config(numel, K, k, W, wl.lr, wl.momentum, wl.wd,
+                                  stream=torch.cuda.current_stream().cuda_stream, grad_dtype=gd), weights)
+    C = min(16, len(os.sched_getaffinity(0)))
+    cuts = [N * j // C for j in range(C + 1)]
+    parts = [Oracle(w0[a:b], K=K, k=k, W=W, lr=wl.lr, m=wl.momentum, wd=wl.wd, mode="f32")
+             for a, b in zip(cuts[:-1], cuts[1:])]
+    del w0
+
+    def same(name, got, pick):
+        got = got.view(np.int32)
+        for j, o in enumerate(parts):
+            exp = np.asarray(pick(o), np.float32).view(np.int32)
+            seg = got[cuts[j]:cuts[j + 1]]
+            if not np.array_equal(seg, exp):
+                bad = np.nonzero(seg != exp)[0]
+                raise AssertionError("%s: %d elements differ in range %d, first at element %d"
+                                     % (name, bad.size, j, cuts[j] + bad[0]))
+
+    def compare(tag):
+        torch.cuda.synchronize()
+        v = ctx.ssd_get_state()
+        same(tag + " w", host(weights), lambda o: o.w)
+        same(tag + " mom", host(ctx.state_tensors("mom")), lambda o: o.mom)
+        same(tag + " pre", host(ctx.state_tensors("pre")), lambda o: o.pre[0])
+        for i in range(K):
+            wl_i = host(weights) if v.w_local_is_global else host(ctx.state_tensors("w_local", i))
+            same(tag + " w_local[%d]" % i, wl_i, lambda o: o.wl[i])
+            if v.w_loc_where == B.SSD_W_LOC_IN_W_LOCAL:
+                same(tag + " w_loc[%d]" % i, host(ctx.state_tensors("w_local", i)), lambda o: o.wloc[i])
+
+    with ThreadPoolExecutor(C) as ex:
+        for it in range(W + k + 2):
+            p = it % P
+            ctx.ssd_step(tables[p])
+            list(ex.map(lambda j: parts[j].step([g[cuts[j]:cuts[j + 1]] for g in gh[p]]), range(C)))
+            print("  iteration %d done" % it, flush=True)
+            if it == W + k - 1:      # a Pull iteration: w' recorded as the global weight, w_loc in the w' arrays
+                compare("after the Pull (it=%d)" % it)
+            if it == W + k + 1:      # refresh-from-global, then a plain iteration
+                compare("after the refresh (it=%d)" % it)
+    ctx.close()
+    del parts, gh, gsets, gviews, tables, wflat
+    torch.cuda.empty_cache()
+
+
 def test_long_schedule_stays_bit_exact():
     """300 steps-delay iterations (75 Pulls) on the ResNet-56-shaped set: no
     drift between the library and the binary32 oracle, and the binary64
