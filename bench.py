@@ -4,16 +4,19 @@
 A "step" is one ssd_step call: one full iteration of Algorithm 1 of the paper
 for the server and all K workers (server aggregate + momentum-SGD update, K GLU
 local updates, and -- every k-th iteration -- the Pull), as one fused launch.
-The workload is the VGG-16-shaped fp32 parameter set (138,357,544 elements in
-32 tensors, K = 8 workers, delay k = 4), with seeded synthetic weights and
-gradients already resident in HBM.  The timed region holds whole k-cycles so
-that every kind of iteration is weighted as in steady state.
+The headline workload is the VGG-16-shaped fp32 parameter set (138,357,544
+elements in 32 tensors, K = 8 workers, delay k = 4), with seeded synthetic
+weights and gradients already resident in HBM.  With the default 20 (or any
+multiple of k) timed steps every kind of iteration is weighted as in steady
+state.  After the headline run the other benchmark configurations are timed
+in the same process and reported under "all_configs".
 
-Prints ONE JSON line.  value = N / (seconds per step).
+Prints ONE JSON line.  value = N / (seconds per step) of the headline workload.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -22,18 +25,24 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X, published
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE + WRITE_SIZE, scaled by what the same counters read on a copy of
-# known size); see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/ssd_fused_kernel_vgg16_K8_k4.txt: 10,272,960 KiB read + 5,404,592 KiB written
-    ("vgg16", "f32"): 16053813047,
-    # profiles/ssd_fused_kernel_vgg16_K8_k4_bf16_gradients.txt: 8,111,157 KiB read + 5,404,592 KiB written
-    ("vgg16", "bf16"): 13840126685,
-    # profiles/ssd_fused_kernel_resnet50_K8_k5.txt, profiles/ssd_fused_kernel_resnet152_K16_k4.txt
-    ("resnet50", "f32"): 2965884324,
-    ("resnet152_k4", "f32"): 12764143822,
+# rocprofv3 summaries (FETCH_SIZE + WRITE_SIZE per launch of the dominant
+# kernel, scaled by what the same counters read on a copy of known size) for
+# the workloads that have one; the measured traffic in the JSON line is read
+# from these files, never typed in
+PROFILE_OF = {
+    ("vgg16", "f32"): "profiles/ssd_fused_kernel_vgg16_K8_k4.txt",
+    ("vgg16", "bf16"): "profiles/ssd_fused_kernel_vgg16_K8_k4_bf16_gradients.txt",
+    ("resnet50", "f32"): "profiles/ssd_fused_kernel_resnet50_K8_k5.txt",
+    ("resnet152_k4", "f32"): "profiles/ssd_fused_kernel_resnet152_K16_k4.txt",
 }
+
+# the benchmark configurations besides the headline one, and how many timed
+# steps each gets (whole k-cycles)
+OTHER_CONFIGS = (("resnet20", 200), ("resnet56", 200), ("resnet50", 40), ("resnet152_k2", 20),
+                 ("resnet152_k4", 20), ("resnet152_k8", 24))
+# a model whose whole resident state fits the 256 MB last-level cache is bound
+# by launch latency, not by HBM: no roofline fraction is quoted for it
+CACHE_BYTES = 256 * 2 ** 20
 
 
 def bytes_per_element(K, kind, pre_action, from_global, gb=4):
@@ -55,6 +64,183 @@ def bytes_per_element(K, kind, pre_action, from_global, gb=4):
     return (model, moved)
 
 
+def read_profile(path):
+    """The figures of a rocprofv3 summary under profiles/: name of the dominant
+    kernel, its measured HBM traffic and its algorithmic bytes per launch."""
+    text = open(os.path.join(ROOT, path)).read()
+    k = re.search(r"^Dominant kernel (ssd_fused_kernel<[^>]*>)", text, re.M)
+    t = re.search(r"traffic ([\d,]+) B vs algorithmic ([\d,]+) B", text)
+    if not k or not t:
+        raise ValueError("%s: no 'Dominant kernel' / 'traffic ... vs algorithmic ...' line" % path)
+    return {"kernel": k.group(1), "traffic": int(t.group(1).replace(",", "")),
+            "algorithmic": int(t.group(2).replace(",", ""))}
+
+
+def dominant_kernel_name(B, K, gd):
+    """Name of the plain steps-delay kernel as rocprofv3 prints it: template
+    arguments K, gradient element type, stage, pre_weight action, from_global,
+    exact_w_minus, workers per group, prefetch."""
+    G, PF = B.ssd_fused_variant(K)
+    return "ssd_fused_kernel<%d, %d, 2, 0, false, false, %d, %s>" % (K, gd, G, "true" if PF else "false")
+
+
+def variant_name(kind, pa, fg):
+    if kind in (0, 1):
+        return "warmup"
+    return "delay_" + ("keep", "init", "refresh")[pa] + ("_from_global" if fg else "")
+
+
+def run_workload(torch, B, workloads, name, args, steps, warmup, P, overrides=True):
+    """Time `steps` iterations of one workload after `warmup` untimed ones.
+    Returns a dict of results and the objects the caller may still need."""
+    dev = torch.device("cuda", 0)
+    wl = workloads.workload(name)
+    if overrides and args.workers > 0:
+        wl = wl._replace(K=args.workers, name=wl.name + "[K=%d]" % args.workers)
+    if overrides and args.delay >= 0:
+        wl = wl._replace(k=args.delay, name=wl.name + "[k=%d]" % args.delay)
+    numel = workloads.numels(wl.tensors)
+    N, T, K, k, W = sum(numel), len(numel), wl.K, wl.k, wl.W
+    gd = {"f32": B.SSD_GRAD_F32, "bf16": B.SSD_GRAD_BF16, "f16": B.SSD_GRAD_F16}[args.grad_dtype if overrides else "f32"]
+    gb = 4 if gd == B.SSD_GRAD_F32 else 2
+    wflat, offs = workloads.initial_weights(wl, device=dev)
+    weights = workloads.views(wflat, wl.tensors, offs)
+    gsets = [workloads.gradient_set(wl, p, device=dev, skew=args.grad_skew_elems if overrides else 0,
+                                    dtype=B.GRAD_TORCH_DTYPE[gd]) for p in range(P)]
+    gviews = [[workloads.views(g, wl.tensors, offs) for g in gs] for gs in gsets]
+    tables = [B.GradTable(g) for g in gviews]
+
+    stream = torch.cuda.current_stream()
+    chunk = args.chunk_elems if overrides else 0
+    waves = args.waves_per_cu if overrides else 0
+    cfg = B.make_config(numel, K, k, W, wl.lr, wl.momentum, wl.wd, device=0,
+                        stream=stream.cuda_stream, chunk_elems=chunk, waves_per_cu=waves, grad_dtype=gd)
+    ctx = B.Context(cfg, weights)
+    view = ctx.ssd_get_state()
+    unfused = overrides and args.unfused
+    two_streams = overrides and args.two_streams
+
+    # untimed: at least the W SSGD iterations of the warm-up stage and the
+    # first local update (whose kernel variant never runs again)
+    untimed = max(warmup, W + 1 if k > 0 else W)
+    it = 0
+    for _ in range(untimed):
+        ctx.ssd_step(tables[it % P])
+        it += 1
+    torch.cuda.synchronize()
+
+    kinds, events = [], []
+    d = max(it - W, 0)
+    pulls_done = None
+    if two_streams:
+        ctx.ssd_materialize()
+        torch.cuda.synchronize()
+        s_srv, s_wrk = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        kind, pa = B.ssd_step_kind_of(it, W, k, d)
+        fg = ctx.ssd_get_state().w_local_is_global
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        if unfused and kind >= 2 and two_streams:
+            # Fig. 3(b): Push / server update beside the local updates; events
+            # only where Algorithm 1 has a data dependency
+            ctx.ssd_set_stream(s_srv)
+            if pulls_done is not None:
+                s_srv.wait_event(pulls_done)
+                pulls_done = None
+            ctx.ssd_server_aggregate_update(tables[it % P])
+            srv_done = torch.cuda.Event()
+            srv_done.record(s_srv)
+            ctx.ssd_set_stream(s_wrk)
+            for i in range(K):
+                ctx.ssd_worker_glu_update(i, gviews[it % P][i])
+            if kind == 3:
+                s_wrk.wait_event(srv_done)
+                for i in range(K):
+                    ctx.ssd_worker_pull(i)
+                pulls_done = torch.cuda.Event()
+                pulls_done.record(s_wrk)
+        elif unfused and kind >= 2:
+            # same iteration as separate launches: gradients are read twice
+            ctx.ssd_server_aggregate_update(tables[it % P])
+            for i in range(K):
+                ctx.ssd_worker_glu_update(i, gviews[it % P][i])
+            if kind == 3:
+                for i in range(K):
+                    ctx.ssd_worker_pull(i)
+        else:
+            ctx.ssd_step(tables[it % P])
+        e1.record(stream)
+        kinds.append((kind, pa, fg))
+        events.append((e0, e1))
+        it += 1
+        d += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec_per_step = (t1 - t0) / steps
+
+    # per-kernel durations from the HIP events of the timed region.  A Pull
+    # iteration runs the same kernel as a plain one (the Pull moves no data).
+    per_kernel = {}
+    for key, (e0, e1) in zip(kinds, events):
+        per_kernel.setdefault(variant_name(*key), []).append((key, e0.elapsed_time(e1)))
+    variants = {}
+    for vname, lst in per_kernel.items():
+        ms = [x[1] for x in lst]
+        key = lst[0][0]
+        moved = bytes_per_element(K, key[0] if key[0] != 3 else 2, key[1], key[2], gb)[1]
+        avg = sum(ms) / len(ms)
+        variants[vname] = {"launches": len(ms), "avg_ms": round(avg, 4), "min_ms": round(min(ms), 4),
+                           "median_ms": round(sorted(ms)[len(ms) // 2], 4),
+                           "bytes_per_elem_moved": moved,
+                           "GBps": round(moved * N / (avg * 1e-3) / 1e9, 1)}
+    dom_name = "delay_keep" if "delay_keep" in variants else max(variants, key=lambda q: variants[q]["launches"])
+    model_bytes = sum(bytes_per_element(K, *q, gb)[0] for q in kinds) * N / len(kinds)
+    moved_bytes = sum(bytes_per_element(K, *q, gb)[1] for q in kinds) * N / len(kinds)
+
+    # the same number of steps again as bare ssd_step calls: no events, no
+    # state queries between them (what a training loop would do); matters only
+    # for the small, launch-bound workloads
+    bare_ms = None
+    if not unfused:
+        seq = [tables[(it + j) % P] for j in range(steps)]
+        torch.cuda.synchronize()
+        tb0 = time.perf_counter()
+        for tb in seq:
+            ctx.ssd_step(tb)
+        torch.cuda.synchronize()
+        bare_ms = (time.perf_counter() - tb0) / steps * 1e3
+        it += steps
+
+    resident = ((2 * K + 3) * 4 + K * gb * P + 4) * N   # state arrays, gradient sets, weights
+    return {"wl": wl, "numel": numel, "N": N, "T": T, "K": K, "k": k, "W": W, "gd": gd, "gb": gb,
+            "wflat": wflat, "offs": offs, "weights": weights, "gsets": gsets, "gviews": gviews,
+            "tables": tables, "ctx": ctx, "view": view, "stream": stream, "it": it,
+            "untimed": untimed, "steps": steps, "sec_per_step": sec_per_step, "bare_ms": bare_ms,
+            "variants": variants, "dom_name": dom_name, "model_bytes": model_bytes,
+            "moved_bytes": moved_bytes, "resident_bytes": resident,
+            "whole_k_cycles": k == 0 or steps % k == 0}
+
+
+def config_line(B, r):
+    """One entry of all_configs."""
+    dom = r["variants"][r["dom_name"]]
+    launch_bound = r["resident_bytes"] <= CACHE_BYTES
+    return {"workload": r["wl"].name, "N": r["N"], "T": r["T"], "K": r["K"], "k": r["k"],
+            "steps": r["steps"], "warmup": r["untimed"],
+            "ms_per_step": round(r["sec_per_step"] * 1e3, 5),
+            "ms_per_step_uninstrumented_repeat": None if r["bare_ms"] is None else round(r["bare_ms"], 5),
+            "elements_per_s": r["N"] / r["sec_per_step"],
+            "elements_per_s_uninstrumented_repeat": None if r["bare_ms"] is None else r["N"] / (r["bare_ms"] * 1e-3),
+            "dominant_kernel": dominant_kernel_name(B, r["K"], r["gd"]),
+            "dominant_kernel_avg_ms": dom["avg_ms"], "dominant_kernel_GBps": dom["GBps"],
+            "bytes_per_elem_moved": dom["bytes_per_elem_moved"],
+            "frac": "launch-bound" if launch_bound else round(dom["GBps"] / HBM_PEAK_GBS, 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +259,8 @@ def main():
     ap.add_argument("--pool", type=int, default=2, help="distinct gradient sets cycled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-probe", action="store_true")
+    ap.add_argument("--no-all-configs", action="store_true",
+                    help="time the headline workload only")
     ap.add_argument("--grad-skew-elems", type=int, default=0,
                     help="worker i's gradient buffer starts i*skew elements into its allocation")
     ap.add_argument("--cpu-sample-elems", type=int, default=64 * 1024 * 1024)
@@ -86,7 +274,6 @@ def main():
         sys.exit("bench.py: this build is a one-GPU build (K workers are K resident sets of "
                  "arrays on one GPU); --gpus %d is not supported, use --gpus 1" % args.gpus)
 
-    import numpy as np
     import torch
     from paper_2012_05396_amd import binding as B
     from paper_2012_05396_amd import workloads
@@ -94,41 +281,32 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
-    wl = workloads.workload(args.workload)
-    if args.workers > 0:
-        wl = wl._replace(K=args.workers, name=wl.name + "[K=%d]" % args.workers)
-    if args.delay >= 0:
-        wl = wl._replace(k=args.delay, name=wl.name + "[k=%d]" % args.delay)
-    numel = workloads.numels(wl.tensors)
-    N, T, K, k, W = sum(numel), len(numel), wl.K, wl.k, wl.W
-
-    wflat, offs = workloads.initial_weights(wl, device=dev)
-    weights = workloads.views(wflat, wl.tensors, offs)
-    P = args.pool
-    gd = {"f32": B.SSD_GRAD_F32, "bf16": B.SSD_GRAD_BF16, "f16": B.SSD_GRAD_F16}[args.grad_dtype]
-    gb = 4 if gd == B.SSD_GRAD_F32 else 2
-    gsets = [workloads.gradient_set(wl, p, device=dev, skew=args.grad_skew_elems,
-                                    dtype=B.GRAD_TORCH_DTYPE[gd]) for p in range(P)]
-    gviews = [[workloads.views(g, wl.tensors, offs) for g in gs] for gs in gsets]
-    tables = [B.GradTable(g) for g in gviews]
-
-    stream = torch.cuda.current_stream()
-    cfg = B.make_config(numel, K, k, W, wl.lr, wl.momentum, wl.wd, device=0,
-                        stream=stream.cuda_stream, chunk_elems=args.chunk_elems,
-                        waves_per_cu=args.waves_per_cu, grad_dtype=gd)
-    ctx = B.Context(cfg, weights)
-    view = ctx.ssd_get_state()
     props = torch.cuda.get_device_properties(dev)
+    P = args.pool
+    overridden = bool(args.workers > 0 or args.delay >= 0 or args.chunk_elems or args.waves_per_cu or
+                      args.unfused or args.grad_skew_elems)
 
-    # untimed: the W SSGD iterations of the warm-up stage plus whole k-cycles
-    untimed = max(args.warmup, W)
-    if k > 0:
-        untimed = W + -(-(untimed - W) // k) * k
-    it = 0
-    for _ in range(untimed):
-        ctx.ssd_step(tables[it % P])
-        it += 1
-    torch.cuda.synchronize()
+    r = run_workload(torch, B, workloads, args.workload, args, args.steps, args.warmup, P)
+    wl, N, T, K, k, W, gd, gb = (r[x] for x in ("wl", "N", "T", "K", "k", "W", "gd", "gb"))
+    ctx, tables, stream, it = r["ctx"], r["tables"], r["stream"], r["it"]
+    value = N / r["sec_per_step"]
+    dom = r["variants"][r["dom_name"]]
+
+    # HBM bytes of one launch of the dominant kernel as the memory counters saw
+    # them: from the rocprofv3 summary of this workload, if there is one for
+    # the kernel that ran and nothing about the run was overridden
+    traffic = traffic_source = None
+    prof = PROFILE_OF.get((args.workload, args.grad_dtype))
+    if prof and not overridden and r["dom_name"] == "delay_keep":
+        pr = read_profile(prof)
+        if pr["kernel"] == dominant_kernel_name(B, K, gd) and pr["algorithmic"] == dom["bytes_per_elem_moved"] * N:
+            traffic, traffic_source = pr["traffic"], prof
+    roofline = {"bound": "hbm", "kernel": dominant_kernel_name(B, K, gd) + " (%s)" % r["dom_name"],
+                "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4),
+                "algorithmic_bytes_per_launch": dom["bytes_per_elem_moved"] * N,
+                "avg_launch_ms": dom["avg_ms"],
+                "traffic": traffic, "traffic_source": traffic_source}
 
     # practical ceiling and counter calibration: a plain copy of known size
     # (2^28 floats: 1 GiB read + 1 GiB written per launch), outside the timed region
@@ -149,102 +327,6 @@ def main():
         probe = {"kernel": "ssd_probe_copy_kernel", "bytes_per_launch": 8 * n_probe,
                  "avg_ms": round(ms, 4), "GBps": round(8 * n_probe / (ms * 1e-3) / 1e9, 1)}
         del src, dst
-
-    kinds, events = [], []
-    d = it - W
-    pulls_done = None
-    if args.two_streams:
-        ctx.ssd_materialize()
-        torch.cuda.synchronize()
-        s_srv, s_wrk = torch.cuda.Stream(), torch.cuda.Stream()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        kind, pa = B.ssd_step_kind_of(it, W, k, d)
-        fg = ctx.ssd_get_state().w_local_is_global
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        if args.unfused and kind >= 2 and args.two_streams:
-            ctx.ssd_set_stream(s_srv)
-            if pulls_done is not None:
-                s_srv.wait_event(pulls_done)
-                pulls_done = None
-            ctx.ssd_server_aggregate_update(tables[it % P])
-            srv_done = torch.cuda.Event()
-            srv_done.record(s_srv)
-            ctx.ssd_set_stream(s_wrk)
-            for i in range(K):
-                ctx.ssd_worker_glu_update(i, gviews[it % P][i])
-            if kind == 3:
-                s_wrk.wait_event(srv_done)
-                for i in range(K):
-                    ctx.ssd_worker_pull(i)
-                pulls_done = torch.cuda.Event()
-                pulls_done.record(s_wrk)
-        elif args.unfused and kind >= 2:
-            # same iteration as separate launches: gradients are read twice
-            ctx.ssd_server_aggregate_update(tables[it % P])
-            for i in range(K):
-                ctx.ssd_worker_glu_update(i, gviews[it % P][i])
-            if kind == 3:
-                for i in range(K):
-                    ctx.ssd_worker_pull(i)
-        else:
-            ctx.ssd_step(tables[it % P])
-        e1.record(stream)
-        kinds.append((kind, pa, fg))
-        events.append((e0, e1))
-        it += 1
-        d += 1
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    sec_per_step = (t1 - t0) / args.steps
-    value = N / sec_per_step
-
-    # per-kernel durations from the HIP events of the timed region.  A Pull
-    # iteration runs the same kernel as a plain one (the Pull moves no data).
-    def kernel_name(kind, pa, fg):
-        if kind in (0, 1):
-            return "warmup"
-        return "delay_" + ("keep", "init", "refresh")[pa] + ("_from_global" if fg else "")
-    per_kernel = {}
-    for key, (e0, e1) in zip(kinds, events):
-        per_kernel.setdefault(kernel_name(*key), []).append((key, e0.elapsed_time(e1)))
-    variants = {}
-    for name, lst in per_kernel.items():
-        ms = [x[1] for x in lst]
-        key = lst[0][0]
-        moved = bytes_per_element(K, key[0] if key[0] != 3 else 2, key[1], key[2], gb)[1]
-        avg = sum(ms) / len(ms)
-        variants[name] = {"launches": len(ms), "avg_ms": round(avg, 4), "min_ms": round(min(ms), 4),
-                          "median_ms": round(sorted(ms)[len(ms) // 2], 4),
-                          "bytes_per_elem_moved": moved,
-                          "GBps": round(moved * N / (avg * 1e-3) / 1e9, 1)}
-    dom_name = "delay_keep" if "delay_keep" in variants else max(variants, key=lambda q: variants[q]["launches"])
-    dom = variants[dom_name]
-    roofline = {"bound": "hbm", "kernel": "ssd_fused_kernel<K=%d> %s" % (K, dom_name),
-                "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4),
-                "algorithmic_bytes_per_launch": dom["bytes_per_elem_moved"] * N,
-                "avg_launch_ms": dom["avg_ms"],
-                "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.grad_dtype))}
-    model_bytes = sum(bytes_per_element(K, *q, gb)[0] for q in kinds) * N / len(kinds)
-    moved_bytes = sum(bytes_per_element(K, *q, gb)[1] for q in kinds) * N / len(kinds)
-
-    # the same number of steps again as bare ssd_step calls: no events, no
-    # state queries between them (what a training loop would do); matters only
-    # for the small, launch-bound workloads
-    bare_ms = None
-    if not args.unfused:
-        seq = [tables[(it + j) % P] for j in range(args.steps)]
-        torch.cuda.synchronize()
-        tb0 = time.perf_counter()
-        for tb in seq:
-            ctx.ssd_step(tb)
-        torch.cuda.synchronize()
-        bare_ms = (time.perf_counter() - tb0) / args.steps * 1e3
-        it += args.steps
 
     # optionally: whole k-cycles captured once into a HIP graph and replayed
     graph_ms = None
@@ -279,9 +361,9 @@ def main():
     # the warm-up (SSGD) iteration, reported separately: the same kernel runs
     # for ever in a context with k = 0, here on the same weights and gradients
     ctx.close()
-    cfg0 = B.make_config(numel, K, 0, 0, wl.lr, wl.momentum, wl.wd, device=0, stream=stream.cuda_stream,
+    cfg0 = B.make_config(r["numel"], K, 0, 0, wl.lr, wl.momentum, wl.wd, device=0, stream=stream.cuda_stream,
                          chunk_elems=args.chunk_elems, waves_per_cu=args.waves_per_cu, grad_dtype=gd)
-    ctx0 = B.Context(cfg0, weights)
+    ctx0 = B.Context(cfg0, r["weights"])
     for i in range(3):
         ctx0.ssd_step(tables[i % P])
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
@@ -301,14 +383,18 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(wl, N, K, k, W, wflat, gsets, offs, numel, args.cpu_sample_elems)
+        cpu = cpu_baseline(wl, N, K, k, W, r["wflat"], r["gsets"], r["offs"], r["numel"], args.cpu_sample_elems)
 
+    headline_line = config_line(B, r)
+    view = r["view"]
     out = {
         "metric": "param-elements updated/s per full SSD-SGD step" + (" (UNFUSED piecewise calls)" if args.unfused else "")
                   + ("" if gb == 4 else " (EXTENSION: %s gradient buffers)" % args.grad_dtype),
-        "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": untimed,
-        "ms_per_step": sec_per_step * 1e3, "ms_per_step_uninstrumented_repeat": bare_ms,
+        "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": r["untimed"], "warmup_requested": args.warmup,
+        "ms_per_step": r["sec_per_step"] * 1e3, "ms_per_step_uninstrumented_repeat": r["bare_ms"],
         "ms_per_step_graph_replay": graph_ms,
+        "timed_steps_are_whole_k_cycles": r["whole_k_cycles"],
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s-shaped fp32 parameter set, N=%d elements in T=%d tensors, "
@@ -319,12 +405,12 @@ def main():
                    "gradient_sets_cycled": P, "seed": wl.seed, "lr": wl.lr, "momentum": wl.momentum,
                    "wd": wl.wd, "device": props.name, "compute_units": props.multi_processor_count,
                    "arch": getattr(props, "gcnArchName", None)},
-        "bytes_per_elem_cycle_average": {"explicit_arrays_model": round(model_bytes / N, 2),
-                                         "moved": round(moved_bytes / N, 2)},
-        "hbm_GBps_cycle_average_moved": round(moved_bytes / sec_per_step / 1e9, 1),
-        "hbm_GBps_cycle_average_model": round(model_bytes / sec_per_step / 1e9, 1),
+        "bytes_per_elem_cycle_average": {"explicit_arrays_model": round(r["model_bytes"] / N, 2),
+                                         "moved": round(r["moved_bytes"] / N, 2)},
+        "hbm_GBps_cycle_average_moved": round(r["moved_bytes"] / r["sec_per_step"] / 1e9, 1),
+        "hbm_GBps_cycle_average_model": round(r["model_bytes"] / r["sec_per_step"] / 1e9, 1),
         "weight_elements_written_per_s": (K + 1) * value,
-        "variants": variants,
+        "variants": r["variants"],
         "warmup_ssgd_iteration": warmup_variant,
         "roofline": roofline,
         "cpu_baseline": cpu,
@@ -332,13 +418,29 @@ def main():
         "context": "the paper reports no number for this path; its end-to-end speedups (up to 110% "
                    "over SSGD) are on 4 x (4 x V100, no NVLink) + 56 Gb/s InfiniBand",
     }
+
+    # the other benchmark configurations, same process, same protocol
+    if not args.no_all_configs and not overridden and args.workload == "vgg16" and args.grad_dtype == "f32":
+        del ctx, ctx0, tables
+        for key in ("wflat", "weights", "gsets", "gviews", "tables", "ctx"):
+            r.pop(key)
+        torch.cuda.empty_cache()
+        lines = []
+        for name, nsteps in OTHER_CONFIGS:
+            q = run_workload(torch, B, workloads, name, args, nsteps, 10, P, overrides=False)
+            q["ctx"].close()
+            lines.append(config_line(B, q))
+            del q
+            torch.cuda.empty_cache()
+        lines.insert(3, headline_line)
+        out["all_configs"] = lines
     print(json.dumps(out))
 
 
 def cpu_baseline(wl, N, K, k, W, wflat, gsets, offs, numel, sample_elems):
     """Time the CPU oracle (binary32, GPU-order build, as it stands, one
-    thread) on the first `sample_elems` elements of the same workload for two
-    whole k-cycles of steps-delay iterations."""
+    thread) on the first `sample_elems` elements of the same workload for
+    four whole k-cycles of steps-delay iterations."""
     import numpy as np
     import torch
     from oracle.ssd_oracle import Oracle

@@ -108,7 +108,7 @@ typedef struct {
                               floats); else a multiple of 256                 */
     int32_t waves_per_cu;  /* cap on wavefronts resident per compute unit in
                               the fused launch; 0 = the library's measured
-                              choice per kernel                               */
+                              choice per kernel (see ssd_lds_slice_bytes)     */
     int32_t grad_sync_exact; /* 0: grad_sync from (pre_weight - w') as printed
                               in Sec. 3.3; 1: from the exact w_minus of
                               Sec. 3.2.1, ((1 - lr*wd)*pre_weight - w')       */
@@ -142,6 +142,16 @@ typedef struct {
     float *w_local;         /* device: w'_i, K arrays (see w_local_is_global)  */
     float *w_loc;           /* device: K arrays, valid when w_loc_where says   */
 } ssd_state_view;
+
+/* Fill *cfg with the paper's settings for K workers and a global learning rate
+ * lr: loc_lr = 4 * lr, alpha = 2.0, beta = 0.5 (Sec. 4.1, "Hyper-parameters");
+ * rescale_grad = 1/K, the averaged gradient the servers apply (Table 1; the
+ * 1/K of Eq. (server)); wd for the servers and, as Eq. (glu-update) prints the
+ * same symbol, for the local update (wd_loc).  Everything else is zeroed:
+ * binary32 gradients, no warm-up, delay_k = 0, the library's choices for
+ * chunk_elems and waves_per_cu, stream NULL.  The caller then sets delay_k,
+ * warmup_iters, momentum, the tensor list, device and stream.  Host-only. */
+int ssd_config_defaults(ssd_config *cfg, int32_t num_workers, float lr, float wd);
 
 /* Bytes of device workspace ssd_init needs for this configuration (state
  * arrays, chunk table, pointer tables).  Host-only; touches no GPU. */
@@ -218,8 +228,13 @@ int ssd_step(ssd_ctx *ctx, const void *const *const *grads);
  * piecewise calls do this themselves when needed; no-op otherwise. */
 int ssd_materialize(ssd_ctx *ctx);
 
-/* Change the learning rates (schedules); grad_sync uses the new global lr
- * from the next call on. */
+/* Change the learning rates (schedules).  lr is the global learning rate in
+ * the parameter servers (Table 1) and therefore also the one inside grad_sync,
+ * which inverts the servers' momentum recursion (Sec. 3.2.1, Sec. 3.3:
+ * grad_sync = (pre_weight - w') * (1-m)/(lr*k)); lr_loc is loc_lr of
+ * Eq. (glu-update).  The paper changes neither during a run; here both take
+ * effect from the next call on, and the constant (1-m)/(lr*k) is formed
+ * again from the new lr.  lr = 0 with delay_k > 0 is SSD_EINVAL. */
 int ssd_set_lr(ssd_ctx *ctx, float lr, float lr_loc);
 
 /* Per-tensor multipliers, as optimisers of deep-learning frameworks keep them
@@ -262,6 +277,26 @@ void ssd_destroy(ssd_ctx *ctx);
  * Returns an ssd_step_kind, or SSD_EINVAL. */
 int ssd_step_kind_of(int64_t iteration, int32_t warmup_iters, int32_t delay_k,
                      int64_t local_updates, int32_t *pre_action);
+
+/* Bytes of LDS that each single-wave workgroup of the fused launch is given,
+ * and never touches, so that at most waves_per_cu of them fit a compute unit
+ * with lds_bytes_per_cu bytes of LDS (163840 on MI355X; ssd_init reads the
+ * device's own value).  LDS is handed out in 128 granules per compute unit, so
+ * the slice is floor(128 / waves_per_cu) granules; the compute unit then holds
+ * floor(128 / floor(128 / waves_per_cu)) waves, which is waves_per_cu itself
+ * for 1..12, 14 and 16 (13 gives 14, 15 gives 16).  0 for waves_per_cu = 0 or
+ * >= 32 (no cap); SSD_EINVAL for a negative count or an LDS size that is not a
+ * positive multiple of 128. */
+int ssd_lds_slice_bytes(int32_t waves_per_cu, int32_t lds_bytes_per_cu);
+
+/* How the fused kernel for K = num_workers is built: *group receives the number
+ * of workers a wave takes at a time (it requests the gradients and local
+ * weights of that many workers, updates them, then goes on to the next group,
+ * carrying the gradient sum in worker order), *prefetch whether the next
+ * group's loads are requested before the current group's arithmetic.  Both
+ * appear as the last two template arguments of ssd_fused_kernel in profiler
+ * output.  Either pointer may be NULL. */
+int ssd_fused_variant(int32_t num_workers, int32_t *group, int32_t *prefetch);
 
 /* Work chunk of the multi-tensor launch: `len` elements of tensor `tensor`
  * starting at element `offset` of that tensor. */

@@ -57,6 +57,9 @@ def _load():
     lib = C.CDLL(LIB_PATH)
     P = C.POINTER
     sigs = {
+        "ssd_config_defaults": (C.c_int, [P(ssd_config), C.c_int32, C.c_float, C.c_float]),
+        "ssd_lds_slice_bytes": (C.c_int, [C.c_int32, C.c_int32]),
+        "ssd_fused_variant": (C.c_int, [C.c_int32, P(C.c_int32), P(C.c_int32)]),
         "ssd_workspace_bytes": (C.c_int, [P(ssd_config), P(C.c_size_t)]),
         "ssd_init": (C.c_int, [P(ssd_config), P(C.c_void_p), C.c_void_p, C.c_size_t, P(C.c_void_p)]),
         "ssd_server_aggregate_update": (C.c_int, [C.c_void_p, P(C.c_void_p)]),
@@ -124,23 +127,47 @@ def ssd_probe_copy(src, dst, stream=None):
         raise SsdError(rc, "ssd_probe_copy: bad size or alignment")
 
 
-def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=2.0, beta=0.5, wd_loc=None,
+def ssd_config_defaults(K, lr, wd):
+    """ssd_config filled by the library with the paper's settings (Sec. 4.1,
+    Table 1) for K workers, global learning rate lr and weight decay wd."""
+    cfg = ssd_config()
+    _check(lib.ssd_config_defaults(C.byref(cfg), K, lr, wd))
+    return cfg
+
+
+def ssd_lds_slice_bytes(waves_per_cu, lds_bytes_per_cu):
+    n = lib.ssd_lds_slice_bytes(waves_per_cu, lds_bytes_per_cu)
+    if n < 0:
+        raise SsdError(n, "bad argument")
+    return n
+
+
+def ssd_fused_variant(K):
+    """(workers per group, prefetch) of the fused kernel for K workers."""
+    g, pf = C.c_int32(0), C.c_int32(0)
+    rc = lib.ssd_fused_variant(K, C.byref(g), C.byref(pf))
+    if rc != SSD_OK:
+        raise SsdError(rc, "bad argument")
+    return g.value, bool(pf.value)
+
+
+def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=None, beta=None, wd_loc=None,
                 rescale_grad=None, device=0, stream=None, chunk_elems=0, waves_per_cu=0,
                 grad_sync_exact=0, grad_dtype=SSD_GRAD_F32):
-    """ssd_config with the defaults of Sec. 4.1 of the paper (loc_lr = 4*lr,
-    alpha = 2, beta = 0.5) and the averaged gradient (1/K).  Returns the
-    struct; it keeps the numel array alive."""
-    import numpy as np
+    """ssd_config: the library's defaults (ssd_config_defaults: loc_lr = 4*lr,
+    alpha = 2, beta = 0.5, averaged gradient, wd_loc = wd), then whatever the
+    caller overrides.  Returns the struct; it keeps the numel array alive."""
     T = len(numel)
     arr = (C.c_int64 * T)(*[int(n) for n in numel])
-    cfg = ssd_config(
-        num_workers=K, delay_k=k, warmup_iters=W, lr=lr, momentum=momentum, wd=wd,
-        lr_loc=float(np.float32(4.0) * np.float32(lr)) if lr_loc is None else lr_loc,
-        alpha=alpha, beta=beta, wd_loc=wd if wd_loc is None else wd_loc,
-        rescale_grad=float(np.float32(1.0 / max(K, 1))) if rescale_grad is None else rescale_grad,
-        num_tensors=T, numel=arr, device=device,
-        stream=stream, chunk_elems=chunk_elems, waves_per_cu=waves_per_cu,
-        grad_sync_exact=grad_sync_exact, grad_dtype=grad_dtype)
+    cfg = ssd_config_defaults(K, lr, wd)
+    cfg.delay_k, cfg.warmup_iters, cfg.momentum = k, W, momentum
+    for name, val in (("lr_loc", lr_loc), ("alpha", alpha), ("beta", beta), ("wd_loc", wd_loc),
+                      ("rescale_grad", rescale_grad)):
+        if val is not None:
+            setattr(cfg, name, val)
+    cfg.num_tensors, cfg.numel, cfg.device, cfg.stream = T, arr, device, stream
+    cfg.chunk_elems, cfg.waves_per_cu = chunk_elems, waves_per_cu
+    cfg.grad_sync_exact, cfg.grad_dtype = grad_sync_exact, grad_dtype
     cfg._keep = arr
     return cfg
 

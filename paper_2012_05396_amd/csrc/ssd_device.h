@@ -18,27 +18,29 @@
 
 // Workgroups are single wavefronts: the unit of scheduling is then one wave
 // working on one 256-element (1 KiB per array) tile, and the number of waves
-// resident per compute unit can be capped exactly (see ssd_lds_for_waves).
-#ifndef SSD_BLOCK
+// resident per compute unit can be capped exactly (see ssd_lds_slice_bytes).
 #define SSD_BLOCK 64
-#endif
 #define SSD_COPY_BLOCK 256
-// non-temporal hints on the streaming accesses (build-time switches)
-#ifndef SSD_NT_LOAD
-#define SSD_NT_LOAD 1
+
+// Workers per group of the fused kernel (see ssd_fused.hip) and whether the
+// next group's loads are requested before the current group's arithmetic.
+// SSD_GROUP / SSD_PREFETCH override the choice for a measurement build.
+constexpr int ssd_group_of(int K)
+{
+#ifdef SSD_GROUP
+    return SSD_GROUP < K ? SSD_GROUP : K;
+#else
+    return K <= 8 ? K : 8;
 #endif
-#ifndef SSD_NT_STORE
-#define SSD_NT_STORE 1
+}
+constexpr bool ssd_prefetch_of(int K)
+{
+#ifdef SSD_PREFETCH
+    return SSD_PREFETCH != 0;
+#else
+    return false;
 #endif
-// 128-bit stores are emitted as "global_store_dwordx4 ... sc1 nt" (agent scope
-// + non-temporal), which the compiler has no builtin for; measured 1-2 %
-// faster than plain "nt" on MI355X.  The compiler cannot see into the asm, so
-// the wait states the ISA requires between a store of more than 64 bits and a
-// VALU write of its data registers are supplied by the s_nop that follows it.
-// SSD_STORE_ASM=0 falls back to __builtin_nontemporal_store.
-#ifndef SSD_STORE_ASM
-#define SSD_STORE_ASM 1
-#endif
+}
 
 enum { SSD_STAGE_WARMUP = 0, SSD_STAGE_DELAY = 2 };
 
@@ -58,7 +60,10 @@ struct ssd_tensor_desc {
 // round-robin by workgroup id, so the block -> tensor table is stored die-major:
 // entry of block b at (b % 8) * blocks_per_xcd + b / 8.  The 16 entries of one
 // 64-byte line are then used by 16 consecutive workgroups of ONE die instead
-// of being fetched by all eight.
+// of being fetched by all eight.  The die count is a constant of the layout,
+// not a query: HIP reports none, and on a device partitioned into fewer dies
+// the table is read just as correctly, only with the plain locality of a
+// table in block order.
 #define SSD_XCDS 8u
 
 struct ssd_tables {
@@ -120,15 +125,9 @@ struct ssd_fused_args {
 // Streaming kernels with dozens of concurrent read and write streams reach
 // their best HBM throughput on MI355X with only a handful of waves per compute
 // unit (few tiles in flight = a narrow window of every array).  The cap is
-// enforced by giving each single-wave workgroup a slice of the 160 KiB LDS
-// that it never touches: waves * slice <= 160 KiB.  0 = no cap.
-// LDS is handed out in granules of 1280 bytes on this chip (128 granules per
-// compute unit), so the slice is a whole number of granules: floor(128 / n).
-static inline unsigned ssd_lds_for_waves(int waves_per_cu)
-{
-    if (waves_per_cu <= 0 || waves_per_cu >= 32) return 0;
-    return (128u / (unsigned)waves_per_cu) * 1280u;
-}
+// enforced by giving each single-wave workgroup a slice of the compute unit's
+// LDS that it never touches: waves * slice <= LDS per compute unit
+// (ssd_lds_slice_bytes, declared in ssd.h; the LDS size is the device's own).
 
 struct ssd_glu_args {
     ssd_tables tab;
@@ -204,19 +203,11 @@ template <int VW> struct ssd_vec;
 template <> struct ssd_vec<1> {
     static __device__ __forceinline__ void ld(cgfloat *p, float (&x)[1])
     {
-#if SSD_NT_LOAD
         x[0] = __builtin_nontemporal_load(p);
-#else
-        x[0] = *p;
-#endif
     }
     static __device__ __forceinline__ void st(gfloat *p, const float (&x)[1])
     {
-#if SSD_NT_STORE
         __builtin_nontemporal_store(x[0], p);
-#else
-        *p = x[0];
-#endif
     }
 };
 template <> struct ssd_vec<4> {
@@ -225,25 +216,19 @@ template <> struct ssd_vec<4> {
     typedef __attribute__((address_space(1))) const v4 cgv4;
     static __device__ __forceinline__ void ld(cgfloat *p, float (&x)[4])
     {
-#if SSD_NT_LOAD
         v4 v = __builtin_nontemporal_load((cgv4 *)p);
-#else
-        v4 v = *(cgv4 *)p;
-#endif
         x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
     }
     static __device__ __forceinline__ void st(gfloat *p, const float (&x)[4])
     {
         v4 v = {x[0], x[1], x[2], x[3]};
-#if SSD_STORE_ASM == 1
+        // "sc1 nt" (system-coherence bit + non-temporal) is a cache policy the
+        // compiler has no builtin for; measured 1-2 % faster than plain "nt"
+        // on MI355X.  The compiler cannot see into the asm, so the wait
+        // states that the ISA requires between a store of more than 64 bits
+        // and a following VALU write of its data registers (2 on gfx950) are
+        // supplied here: s_nop 1 idles for two cycles.
         asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
-#elif SSD_STORE_ASM == 2
-        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
-#elif SSD_NT_STORE
-        __builtin_nontemporal_store(v, (gv4 *)p);
-#else
-        *(gv4 *)p = v;
-#endif
     }
 };
 
@@ -322,18 +307,23 @@ static inline bool ssd_aligned16_host(const void *p)
     return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
 }
 
+// records a message for ssd_last_error(NULL) on this thread and returns `code`
+int ssd_fail_thread(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // launchers, one translation unit each
 hipError_t ssd_launch_glu(int grad_dtype, int pre_action, unsigned nchunks, hipStream_t s, const ssd_glu_args &a);
 hipError_t ssd_launch_pull(int init, unsigned nchunks, hipStream_t s, const ssd_pull_args &a);
 hipError_t ssd_launch_fill_zero(float *p, int64_t n, hipStream_t s);
+// lds_bytes: LDS slice per workgroup (occupancy cap, 0 = none); lds_limit: the
+// largest slice any launch on this device may ask for (LDS per compute unit)
 typedef hipError_t (*ssd_fused_launcher)(int stage, int pre_action, int from_global, int exact_w_minus,
-                                         int waves_per_cu,
+                                         unsigned lds_bytes, unsigned lds_limit,
                                          unsigned nchunks, hipStream_t s, const ssd_fused_args &a);
 // ssd_launch_fused_g<grad_dtype>_k<K>
 #define SSD_DECL_FUSED(k)                                                                                        \
-    hipError_t ssd_launch_fused_g0_k##k(int, int, int, int, int, unsigned, hipStream_t, const ssd_fused_args &); \
-    hipError_t ssd_launch_fused_g1_k##k(int, int, int, int, int, unsigned, hipStream_t, const ssd_fused_args &); \
-    hipError_t ssd_launch_fused_g2_k##k(int, int, int, int, int, unsigned, hipStream_t, const ssd_fused_args &);
+    hipError_t ssd_launch_fused_g0_k##k(int, int, int, int, unsigned, unsigned, unsigned, hipStream_t, const ssd_fused_args &); \
+    hipError_t ssd_launch_fused_g1_k##k(int, int, int, int, unsigned, unsigned, unsigned, hipStream_t, const ssd_fused_args &); \
+    hipError_t ssd_launch_fused_g2_k##k(int, int, int, int, unsigned, unsigned, unsigned, hipStream_t, const ssd_fused_args &);
 SSD_DECL_FUSED(1) SSD_DECL_FUSED(2) SSD_DECL_FUSED(3) SSD_DECL_FUSED(4)
 SSD_DECL_FUSED(5) SSD_DECL_FUSED(6) SSD_DECL_FUSED(7) SSD_DECL_FUSED(8)
 SSD_DECL_FUSED(9) SSD_DECL_FUSED(10) SSD_DECL_FUSED(11) SSD_DECL_FUSED(12)

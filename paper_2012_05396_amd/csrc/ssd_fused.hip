@@ -11,13 +11,27 @@
 // global weight, so the host only records that fact and the next launch
 // (template flag FG) takes w'_i from the global weight it loads anyway.
 //
+// Workers in groups.  A wave does not request all 2K+3 arrays of its tile at
+// once: it takes the workers in groups of G (template argument; ssd_group_of).
+// For group j it needs g_i and w'_i of the G workers of the group only; the
+// GLU update of worker i depends on nothing else that changes, and the sum of
+// the gradients is carried from group to group in worker order, so the
+// rounding sequence S = g_0; S = S + g_i (i = 1..K-1) is the same as without
+// groups.  That bounds the loads a wave has in flight by the group size, not
+// by K: the best HBM throughput of this many-stream access pattern on MI355X
+// is reached with a nearly constant number of loads in flight per compute
+// unit, whatever K is, and with K = 16 a whole-tile wave overshoots it.
+// With PF the loads of group j+1 are requested before the arithmetic and the
+// stores of group j.
+//
 // Order of issue inside a wave: the loads of the library's own state (momentum,
-// pre_weight, K local weights) need nothing but blockIdx, so they go out first;
-// the two table lookups that lead to the caller's pointers (block -> tensor,
-// tensor -> one record with the weight and K gradient pointers) overlap with
-// them; then the gradient and
-// weight loads; then arithmetic and stores.  128-bit accesses whenever every
-// caller pointer of the tensor is 16-byte aligned, else element by element.
+// pre_weight, the first group's local weights) need nothing but blockIdx, so
+// they go out first; the two table lookups that lead to the caller's pointers
+// (block -> tensor, tensor -> one record with the weight and K gradient
+// pointers) overlap with them; then the first group's gradient loads and the
+// weight load; then, group by group, arithmetic and stores.  128-bit accesses
+// whenever every caller pointer of the tensor is 16-byte aligned, else element
+// by element.
 //
 // Compiled once per K (-DSSD_K=1..16) so that the worker loops unroll, and per
 // element type of the gradient buffers (-DSSD_GD=0..2).
@@ -30,90 +44,131 @@
 #error "compile with -DSSD_GD=<ssd_grad_dtype of the gradient buffers>"
 #endif
 
-template <int K, int VW> struct ssd_state_regs {
-    float mo[VW], p[VW], wl[K][VW];
+// registers of one group of workers: their local weights and gradients
+template <int G, int VW> struct ssd_group_regs {
+    float wl[G][VW], g[G][VW];
 };
 
-template <int K, int STAGE, int PRE, bool FG, int VW>
-__device__ __forceinline__ void ssd_load_state(const ssd_fused_args &a, gfloat *momp, gfloat *prep,
-                                               gfloat *wlp, unsigned e, ssd_state_regs<K, VW> &s)
+// state of the tile that is requested before the table lookups return
+template <int G, int VW> struct ssd_head_regs {
+    float mo[VW], p[VW];
+    ssd_group_regs<G, VW> grp; // .wl of group 0
+};
+
+template <int K, int STAGE, bool FG, int G, int VW>
+__device__ __forceinline__ void ssd_load_wl(int j, gfloat *wlp, int64_t A, unsigned e,
+                                            ssd_group_regs<G, VW> &r)
 {
-    typedef ssd_vec<VW> V;
-    V::ld(momp + e, s.mo);
-    if (STAGE == SSD_STAGE_DELAY) {
-        if (PRE != SSD_PRE_INIT) V::ld(prep + e, s.p);
-        if (!FG) {
+    if (STAGE == SSD_STAGE_DELAY && !FG) {
 #pragma unroll
-            for (int i = 0; i < K; ++i) V::ld(wlp + i * a.A + e, s.wl[i]);
-        }
+        for (int i = 0; i < G; ++i)
+            if (j * G + i < K) ssd_vec<VW>::ld(wlp + (int64_t)(j * G + i) * A + e, r.wl[i]);
     }
 }
 
-template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int VW>
-__device__ __forceinline__ void ssd_finish(const ssd_fused_args &a, const ssd_hyper &h,
-                                           const typename ssd_gvec<GD, 4>::ptr (&gp)[K], gfloat *wp, gfloat *momp,
-                                           gfloat *prep, gfloat *wlp, unsigned e,
-                                           const ssd_state_regs<K, VW> &s)
+template <int K, int GD, int G, int VW>
+__device__ __forceinline__ void ssd_load_g(int j, const typename ssd_gvec<GD, 4>::ptr (&gp)[K], unsigned e,
+                                           ssd_group_regs<G, VW> &r)
+{
+#pragma unroll
+    for (int i = 0; i < G; ++i)
+        if (j * G + i < K) ssd_gvec<GD, VW>::ld(gp[j * G + i] + e, r.g[i]);
+}
+
+template <int K, int STAGE, int PRE, bool FG, int G, int VW>
+__device__ __forceinline__ void ssd_load_head(gfloat *momp, gfloat *prep, gfloat *wlp, int64_t A, unsigned e,
+                                              ssd_head_regs<G, VW> &s)
+{
+    ssd_vec<VW>::ld(momp + e, s.mo);
+    if (STAGE == SSD_STAGE_DELAY) {
+        if (PRE != SSD_PRE_INIT) ssd_vec<VW>::ld(prep + e, s.p);
+        ssd_load_wl<K, STAGE, FG, G, VW>(0, wlp, A, e, s.grp);
+    }
+}
+
+// Elements e .. e+VW-1 of the tile, given the head state in `s`.
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF, int VW>
+__device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ssd_gvec<GD, 4>::ptr (&gp)[K],
+                                           gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t A,
+                                           unsigned e, const ssd_head_regs<G, VW> &s)
 {
     typedef ssd_vec<VW> V;
-    float g[K][VW], w[VW];
-#pragma unroll
-    for (int i = 0; i < K; ++i) ssd_gvec<GD, VW>::ld(gp[i] + e, g[i]);
+    constexpr int NG = (K + G - 1) / G;
+    ssd_group_regs<G, VW> cur = s.grp;
+    float w[VW], S[VW];
+    ssd_load_g<K, GD, G, VW>(0, gp, e, cur);
     V::ld(wp + e, w);
+
+#pragma unroll
+    for (int j = 0; j < NG; ++j) {
+        ssd_group_regs<G, VW> nxt = {};
+        if (PF && j + 1 < NG) {
+            ssd_load_wl<K, STAGE, FG, G, VW>(j + 1, wlp, A, e, nxt);
+            ssd_load_g<K, GD, G, VW>(j + 1, gp, e, nxt);
+        }
+        // Eq. (server): the sum of the K gradients, in worker order
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            if (j * G + i < K) {
+#pragma unroll
+                for (int v = 0; v < VW; ++v) S[v] = (j * G + i == 0) ? cur.g[i][v] : S[v] + cur.g[i][v];
+            }
+        }
+        if (STAGE == SSD_STAGE_DELAY) {
+            // FG: every w'_i is the global weight as it stood before this
+            // iteration's server update (after a Pull, or at the end of warm-up),
+            // which is in registers already; the w' arrays are not read.
+            // Alg. 2: pre_weight takes w' as it was before this update.
+            if (j == 0 && PRE != SSD_PRE_KEEP) V::st(prep + e, FG ? w : cur.wl[0]);
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                if (j * G + i < K) {
+                    float r[VW];
+#pragma unroll
+                    for (int v = 0; v < VW; ++v) {
+                        const float wli = FG ? w[v] : cur.wl[i][v];
+                        const float pv = (PRE == SSD_PRE_INIT) ? wli : s.p[v];
+                        r[v] = ssd_glu_elem<XW>(cur.g[i][v], wli, pv, h);
+                    }
+                    V::st(wlp + (int64_t)(j * G + i) * A + e, r);
+                }
+            }
+        }
+        if (!PF && j + 1 < NG) {
+            ssd_load_wl<K, STAGE, FG, G, VW>(j + 1, wlp, A, e, nxt);
+            ssd_load_g<K, GD, G, VW>(j + 1, gp, e, nxt);
+        }
+        if (j + 1 < NG) cur = nxt;
+    }
 
     float wn[VW], mn[VW];
 #pragma unroll
-    for (int v = 0; v < VW; ++v) {
-        float S = g[0][v];
-#pragma unroll
-        for (int i = 1; i < K; ++i) S = S + g[i][v];
-        ssd_server_elem(S, w[v], s.mo[v], h, wn[v], mn[v]);
-    }
+    for (int v = 0; v < VW; ++v) ssd_server_elem(S[v], w[v], s.mo[v], h, wn[v], mn[v]);
     V::st(momp + e, mn);
     V::st(wp + e, wn);
-
-    if (STAGE == SSD_STAGE_DELAY) {
-        // FG: every w'_i is the global weight as it stood before this
-        // iteration's server update (after a Pull, or at the end of warm-up),
-        // which is in registers already; the w' arrays are not read.
-        // Alg. 2: pre_weight takes w' as it was before this update.
-        if (PRE != SSD_PRE_KEEP) V::st(prep + e, FG ? w : s.wl[0]);
-#pragma unroll
-        for (int i = 0; i < K; ++i) {
-            float r[VW];
-#pragma unroll
-            for (int v = 0; v < VW; ++v) {
-                const float wli = FG ? w[v] : s.wl[i][v];
-                const float pv = (PRE == SSD_PRE_INIT) ? wli : s.p[v];
-                r[v] = ssd_glu_elem<XW>(g[i][v], wli, pv, h);
-            }
-            V::st(wlp + i * a.A + e, r);
-        }
-    }
 }
 
 // One 256-element tile: lane l owns elements e0 .. e0+3 (e0 = base + 4l).
 // Full vectors take the 128-bit path; a lane at the ragged end of the block,
 // or any lane when a caller pointer is not 16-byte aligned, goes element by
-// element -- in both cases with the state values preloaded in `s`.
-template <int K, int GD, int STAGE, int PRE, bool FG, bool XW>
-__device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, const ssd_hyper &h,
-                                         const typename ssd_gvec<GD, 4>::ptr (&gp)[K], gfloat *wp, gfloat *momp,
-                                         gfloat *prep, gfloat *wlp, unsigned e0, unsigned len, bool vec,
-                                         const ssd_state_regs<K, 4> &s)
+// element -- in both cases with the head state preloaded in `s`.
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF>
+__device__ __forceinline__ void ssd_tile(const ssd_hyper &h, const typename ssd_gvec<GD, 4>::ptr (&gp)[K],
+                                         gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t A,
+                                         unsigned e0, unsigned len, bool vec, const ssd_head_regs<G, 4> &s)
 {
     if (vec && e0 + 3 < len) {
-        ssd_finish<K, GD, STAGE, PRE, FG, XW, 4>(a, h, gp, wp, momp, prep, wlp, e0, s);
+        ssd_finish<K, GD, STAGE, PRE, FG, XW, G, PF, 4>(h, gp, wp, momp, prep, wlp, A, e0, s);
     } else if (e0 < len) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             if (e0 + v < len) {
-                ssd_state_regs<K, 1> s1;
+                ssd_head_regs<G, 1> s1;
                 s1.mo[0] = s.mo[v];
                 s1.p[0] = s.p[v];
 #pragma unroll
-                for (int i = 0; i < K; ++i) s1.wl[i][0] = s.wl[i][v];
-                ssd_finish<K, GD, STAGE, PRE, FG, XW, 1>(a, h, gp, wp, momp, prep, wlp, e0 + v, s1);
+                for (int i = 0; i < G; ++i) s1.grp.wl[i][0] = s.grp.wl[i][v];
+                ssd_finish<K, GD, STAGE, PRE, FG, XW, G, false, 1>(h, gp, wp, momp, prep, wlp, A, e0 + v, s1);
             }
         }
     }
@@ -122,7 +177,7 @@ __device__ __forceinline__ void ssd_tile(const ssd_fused_args &a, const ssd_hype
 // The arguments a wave needs first come as separate leading kernel arguments
 // so that they can be preloaded into scalar registers at wave launch
 // (-amdgpu-kernarg-preload-count); the rest arrives with ordinary scalar loads.
-template <int K, int GD, int STAGE, int PRE, bool FG, bool XW>
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF>
 __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *block_tensor, float *mom,
                                                               float *pre, float *wl, int64_t A,
                                                               unsigned C, unsigned blocks_per_xcd,
@@ -130,37 +185,25 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
                                                               const ssd_tensor_hyper *thyper,
                                                               const ssd_hyper hglobal)
 {
-    ssd_fused_args a;
-    a.tab.block_tensor = block_tensor;
-    a.tab.tensors = nullptr;
-    a.tab.C = C;
-    a.tab.blocks_per_xcd = blocks_per_xcd;
-    a.rec = rec_table;
-    a.mom = mom;
-    a.pre = pre;
-    a.wl = wl;
-    a.A = A;
-    a.thyper = thyper;
-    a.h = hglobal;
     const unsigned lane = threadIdx.x;
     // head of the lookup chain: request it first
-    const int t = a.tab.block_tensor[ssd_block_slot(blockIdx.x, a.tab.blocks_per_xcd)];
+    const int t = block_tensor[ssd_block_slot(blockIdx.x, blocks_per_xcd)];
     // state arrays: addressed by blockIdx alone, always 16-byte aligned, and
     // padded to whole blocks, so the first tile is requested right away
-    const int64_t ao = (int64_t)blockIdx.x * a.tab.C;
-    gfloat *momp = ssd_global(a.mom) + ao, *prep = ssd_global(a.pre) + ao;
-    gfloat *wlp = ssd_global(a.wl) + ao;
-    ssd_state_regs<K, 4> s;
-    ssd_load_state<K, STAGE, PRE, FG, 4>(a, momp, prep, wlp, lane * 4, s);
+    const int64_t ao = (int64_t)blockIdx.x * C;
+    gfloat *momp = ssd_global(mom) + ao, *prep = ssd_global(pre) + ao;
+    gfloat *wlp = ssd_global(wl) + ao;
+    ssd_head_regs<G, 4> s;
+    ssd_load_head<K, STAGE, PRE, FG, G, 4>(momp, prep, wlp, A, lane * 4, s);
 
     // block -> tensor -> one record {w, first_block, numel, g_0 .. g_{K-1}}
     // and the tensor's hyper-parameters
-    const ssd_hyper h = ssd_hyper_of(a.h, a.thyper[t]);
-    const int64_t *rec = a.rec + (int64_t)t * (K + 3);
+    const ssd_hyper h = ssd_hyper_of(hglobal, thyper[t]);
+    const int64_t *rec = rec_table + (int64_t)t * (K + 3);
     float *w = reinterpret_cast<float *>(rec[0]);
-    const int64_t off = ((int64_t)blockIdx.x - rec[1]) * a.tab.C;
+    const int64_t off = ((int64_t)blockIdx.x - rec[1]) * C;
     const int64_t left = rec[2] - off;
-    const unsigned len = left < (int64_t)a.tab.C ? (unsigned)left : a.tab.C;
+    const unsigned len = left < (int64_t)C ? (unsigned)left : C;
     typedef typename ssd_gvec<GD, 4>::ptr gptr;
     gptr gp[K];
     bool vec = ssd_aligned16(w);
@@ -174,31 +217,52 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
 
     unsigned base = 0;
     for (;;) {
-        ssd_tile<K, GD, STAGE, PRE, FG, XW>(a, h, gp, wp, momp, prep, wlp, base + lane * 4, len, vec, s);
+        ssd_tile<K, GD, STAGE, PRE, FG, XW, G, PF>(h, gp, wp, momp, prep, wlp, A, base + lane * 4, len, vec, s);
         base += SSD_BLOCK * 4;
         if (base >= len) break; // uniform
-        ssd_load_state<K, STAGE, PRE, FG, 4>(a, momp, prep, wlp, base + lane * 4, s);
+        ssd_load_head<K, STAGE, PRE, FG, G, 4>(momp, prep, wlp, A, base + lane * 4, s);
     }
 }
 
 #define SSD_CAT2(a, b) a##b
 #define SSD_CAT(a, b) SSD_CAT2(a, b)
 
+// A slice of LDS above 64 KiB needs the kernel's dynamic-LDS limit raised;
+// that is a property of the kernel on a device, set once per kernel variant
+// and device (bit d of `done`), not per launch.
+template <typename Kernel>
+static hipError_t ssd_allow_lds(Kernel kernel, unsigned lds, unsigned long long &done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done & bit) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds);
+    if (e == hipSuccess) done |= bit;
+    return e;
+}
+
 hipError_t SSD_CAT(SSD_CAT(SSD_CAT(ssd_launch_fused_g, SSD_GD), _k), SSD_K)(int stage, int pre_action, int from_global, int exact_w_minus,
-                                               int waves_per_cu, unsigned nchunks, hipStream_t s,
+                                               unsigned lds_bytes, unsigned lds_limit, unsigned nchunks, hipStream_t s,
                                                const ssd_fused_args &a)
 {
     const dim3 grid(nchunks), block(SSD_BLOCK);
-    const unsigned lds = ssd_lds_for_waves(waves_per_cu); // occupancy cap only, never accessed
-#define SSD_GO(ST, PR, FG, XW)                                                     \
-    do {                                                                           \
-        if (lds > 65536)                                                           \
-            (void)hipFuncSetAttribute((const void *)ssd_fused_kernel<SSD_K, SSD_GD, ST, PR, FG, XW>, \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        ssd_fused_kernel<SSD_K, SSD_GD, ST, PR, FG, XW><<<grid, block, lds, s>>>(            \
-            a.tab.block_tensor, a.mom, a.pre, a.wl, a.A, a.tab.C, a.tab.blocks_per_xcd, a.rec, a.thyper,  \
-            a.h);                                                                    \
-        return hipGetLastError();                                                  \
+    constexpr int G = ssd_group_of(SSD_K);
+    constexpr bool PF = ssd_prefetch_of(SSD_K);
+    // lds_bytes: the occupancy cap, a slice of LDS that is never accessed
+#define SSD_GO(ST, PR, FG, XW)                                                                     \
+    do {                                                                                           \
+        auto kernel = ssd_fused_kernel<SSD_K, SSD_GD, ST, PR, FG, XW, G, PF>;                      \
+        if (lds_bytes > 65536) {                                                                   \
+            static unsigned long long done = 0;                                                    \
+            const hipError_t e = ssd_allow_lds(kernel, lds_limit, done);                           \
+            if (e != hipSuccess) return e;                                                         \
+        }                                                                                          \
+        kernel<<<grid, block, lds_bytes, s>>>(a.tab.block_tensor, a.mom, a.pre, a.wl, a.A, a.tab.C, \
+                                              a.tab.blocks_per_xcd, a.rec, a.thyper, a.h);         \
+        return hipGetLastError();                                                                  \
     } while (0)
 #define SSD_GO_DELAY(PR, FG)                                                       \
     do {                                                                           \

@@ -31,6 +31,21 @@ int fail_init(int code, const char *fmt, ...)
     return code;
 }
 
+} // namespace
+
+// for the entry points that have no context: the message goes where
+// ssd_last_error(NULL) finds it
+int ssd_fail_thread(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    set_err(g_init_error, sizeof g_init_error, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+namespace {
+
 constexpr size_t kWsAlign = 256;
 constexpr int kFusedSlots = 8;
 
@@ -62,6 +77,7 @@ struct PtrCache {
         ev.assign(n, nullptr);
         up_stream.assign(n, nullptr);
         users.assign(n, std::vector<hipStream_t>());
+        for (auto &u : users) u.reserve(8);
         hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&host), sizeof(int64_t) * len * n,
                                      hipHostMallocDefault);
         if (e != hipSuccess) {
@@ -258,9 +274,21 @@ struct ssd_ctx {
     ssd_tensor_hyper *d_thyper = nullptr, *h_thyper[2] = {nullptr, nullptr};
     hipEvent_t thyper_ev[2] = {nullptr, nullptr};
     int thyper_next = 0;
+    // what the occupancy cap and the small-model rule need to know about the
+    // device, read once at ssd_init
+    int num_cus = 0;
+    int lds_per_cu = 0;
     int64_t it = 0;
     std::vector<int64_t> loc_update;
     std::vector<char> has_local, wloc_fresh;
+    // pre_weight is one shared array (Sec. 3.3: every worker holds the same
+    // value), which is only true while every worker's w' is the same global
+    // weight when pre_weight is initialised or refreshed from it.  w_version
+    // counts the server updates; pulled_version[i] is its value at worker i's
+    // last Pull; round_version that of the first worker of the current
+    // init/refresh round.
+    int64_t w_version = 0, round_version = -1;
+    std::vector<int64_t> pulled_version;
     // After the hand-over at the end of warm-up and after a Pull of the fused
     // step, every w'_i equals the global weight; that is recorded here instead
     // of being written K times.  wl_holds_wloc: the w' arrays then still hold
@@ -341,7 +369,43 @@ int ssd_step_kind_of(int64_t iteration, int32_t W, int32_t k, int64_t d, int32_t
     return d % k == k - 1 ? SSD_STEP_DELAY_PULL : SSD_STEP_DELAY; // Alg. 1: Pull every k
 }
 
-int ssd_plan_chunks(const int64_t *numel, int32_t T, int32_t chunk_elems, ssd_chunk *out,
+int ssd_lds_slice_bytes(int32_t waves_per_cu, int32_t lds_bytes_per_cu)
+{
+    if (waves_per_cu < 0 || lds_bytes_per_cu < 128 || lds_bytes_per_cu % 128) return SSD_EINVAL;
+    if (waves_per_cu == 0 || waves_per_cu >= 32) return 0; // no cap
+    // LDS is handed out in 128 granules per compute unit (1280 bytes each on
+    // gfx950, whose compute units have 160 KiB): a whole number of granules
+    const int granule = lds_bytes_per_cu / 128;
+    return (128 / waves_per_cu) * granule;
+}
+
+int ssd_fused_variant(int32_t num_workers, int32_t *group, int32_t *prefetch)
+{
+    if (num_workers < 1 || num_workers > SSD_MAX_WORKERS) return SSD_EINVAL;
+    if (group) *group = ssd_group_of(num_workers);
+    if (prefetch) *prefetch = ssd_prefetch_of(num_workers) ? 1 : 0;
+    return SSD_OK;
+}
+
+int ssd_config_defaults(ssd_config *cfg, int32_t num_workers, float lr, float wd)
+{
+    if (!cfg) return fail_init(SSD_EINVAL, "cfg is NULL");
+    if (num_workers < 1 || num_workers > SSD_MAX_WORKERS)
+        return fail_init(SSD_EINVAL, "num_workers = %d, must be 1..%d", num_workers, SSD_MAX_WORKERS);
+    std::memset(cfg, 0, sizeof *cfg);
+    cfg->num_workers = num_workers;
+    cfg->lr = lr;
+    cfg->wd = wd;
+    cfg->wd_loc = wd;          // Eq. (glu-update) prints the servers' wd
+    cfg->lr_loc = 4.0f * lr;   // Sec. 4.1: loc_lr is four times the global learning rate
+    cfg->alpha = 2.0f;         // Sec. 4.1
+    cfg->beta = 0.5f;          // Sec. 4.1
+    cfg->rescale_grad = (float)(1.0 / (double)num_workers); // Table 1: the servers' gradient is the average
+    cfg->grad_dtype = SSD_GRAD_F32;
+    return SSD_OK;
+}
+
+static int ssd_plan_chunks_impl(const int64_t *numel, int32_t T, int32_t chunk_elems, ssd_chunk *out,
                     int64_t capacity, int64_t *count, int32_t *used)
 {
     if (!numel || T < 1 || !count) return fail_init(SSD_EINVAL, "ssd_plan_chunks: NULL argument or T < 1");
@@ -364,7 +428,7 @@ int ssd_plan_chunks(const int64_t *numel, int32_t T, int32_t chunk_elems, ssd_ch
     return SSD_OK;
 }
 
-int ssd_workspace_bytes(const ssd_config *cfg, size_t *bytes)
+static int ssd_workspace_bytes_impl(const ssd_config *cfg, size_t *bytes)
 {
     if (!bytes) return fail_init(SSD_EINVAL, "bytes is NULL");
     int rc = check_config(cfg);
@@ -392,7 +456,10 @@ void ssd_destroy(ssd_ctx *ctx)
     delete ctx;
 }
 
-int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size_t workspace_bytes,
+static int init_context(ssd_ctx *c, const ssd_config *cfg, float *const *weights, void *workspace,
+                        size_t workspace_bytes, ssd_ctx **out);
+
+static int ssd_init_impl(const ssd_config *cfg, float *const *weights, void *workspace, size_t workspace_bytes,
              ssd_ctx **out)
 {
     if (!out) return fail_init(SSD_EINVAL, "out is NULL");
@@ -403,7 +470,7 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
     if (!workspace) return fail_init(SSD_EINVAL, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(workspace) % kWsAlign)
         return fail_init(SSD_EALIGN, "workspace is not %zu-byte aligned", kWsAlign);
-    const int T = cfg->num_tensors, K = cfg->num_workers;
+    const int T = cfg->num_tensors;
     for (int t = 0; t < T; ++t) {
         if (!weights[t]) return fail_init(SSD_EINVAL, "weights[%d] is NULL", t);
         if (reinterpret_cast<uintptr_t>(weights[t]) % sizeof(float))
@@ -412,6 +479,21 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
     ssd_ctx *c = new (std::nothrow) ssd_ctx;
     if (!c) return fail_init(SSD_ENOMEM, "host allocation failed");
     c->err[0] = 0;
+    c->cfg = *cfg;
+    c->cfg.numel = nullptr;
+    try {
+        return init_context(c, cfg, weights, workspace, workspace_bytes, out);
+    } catch (...) {
+        ssd_destroy(c); // a host allocation failed half-way
+        throw;
+    }
+}
+
+static int init_context(ssd_ctx *c, const ssd_config *cfg, float *const *weights, void *workspace,
+                        size_t workspace_bytes, ssd_ctx **out)
+{
+    const int T = cfg->num_tensors, K = cfg->num_workers;
+    int rc;
     c->cfg = *cfg;
     c->numel.assign(cfg->numel, cfg->numel + T);
     c->cfg.numel = c->numel.data();
@@ -449,6 +531,7 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
     c->loc_update.assign(K, 0);
     c->has_local.assign(K, 0);
     c->wloc_fresh.assign(K, 0);
+    c->pulled_version.assign(K, -1);
     c->lr_mult.assign(T, 1.0f);
     c->wd_mult.assign(T, 1.0f);
     c->scratch.resize((size_t)T * (K + 3));
@@ -465,6 +548,21 @@ int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size
         return rc;
     }
     hipError_t e;
+    {
+        int v = 0;
+        e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, cfg->device);
+        if (e == hipSuccess) {
+            c->num_cus = v;
+            e = hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, cfg->device);
+        }
+        if (e != hipSuccess || c->num_cus < 1 || v < 1) {
+            rc = fail_init(SSD_EHIP, "cannot read compute-unit count and LDS size of device %d: %s", cfg->device,
+                           hipGetErrorString(e));
+            delete c;
+            return rc;
+        }
+        c->lds_per_cu = v;
+    }
 #define SSD_INIT_HIP(call, what)                                                         \
     do {                                                                                 \
         e = (call);                                                                      \
@@ -589,9 +687,12 @@ static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
         // 256 compute units of MI355X) is over in two or three rounds of waves
         // and its arrays stay in the last-level cache: the cap only delays the
         // tail there (measured 3-6 % slower on 0.27 M- and 0.86 M-element models).
-        if (c->L.num_chunks <= 32 * 256 && waves < 16) waves = 16;
+        if (c->L.num_chunks <= 32 * (int64_t)c->num_cus) waves = 0;
     }
-    e = table[c->cfg.grad_dtype][c->cfg.num_workers - 1](stage, pre_action, from_global, c->cfg.grad_sync_exact, waves,
+    const int lds = ssd_lds_slice_bytes(waves, c->lds_per_cu);
+    if (lds < 0) return c->fail(SSD_EINVAL, "no LDS slice for %d waves per compute unit", waves);
+    e = table[c->cfg.grad_dtype][c->cfg.num_workers - 1](stage, pre_action, from_global, c->cfg.grad_sync_exact,
+                                      (unsigned)lds, (unsigned)c->lds_per_cu,
                                       (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the fused kernel");
     return SSD_OK;
@@ -609,12 +710,13 @@ static int materialize(ssd_ctx *c)
         hipError_t e = ssd_launch_pull(c->wl_holds_wloc ? 0 : 1, (unsigned)c->L.num_chunks, c->stream, a);
         if (e != hipSuccess) return c->fail_hip(e, "launch of the pull kernel");
         c->wloc_fresh[i] = 1;
+        c->pulled_version[i] = c->w_version;
     }
     c->wl_is_global = c->wl_holds_wloc = false;
     return SSD_OK;
 }
 
-int ssd_materialize(ssd_ctx *c)
+static int ssd_materialize_impl(ssd_ctx *c)
 {
     if (!c) return SSD_EINVAL;
     DeviceGuard guard(c->cfg.device);
@@ -622,7 +724,7 @@ int ssd_materialize(ssd_ctx *c)
     return materialize(c);
 }
 
-int ssd_server_aggregate_update(ssd_ctx *c, const void *const *const *grads)
+static int ssd_server_aggregate_update_impl(ssd_ctx *c, const void *const *const *grads)
 {
     if (!c) return SSD_EINVAL;
     int rc = check_grads(c, grads);
@@ -631,10 +733,12 @@ int ssd_server_aggregate_update(ssd_ctx *c, const void *const *const *grads)
     if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
     rc = materialize(c); // the global weight is about to change
     if (rc != SSD_OK) return rc;
-    return launch_fused(c, SSD_STAGE_WARMUP, SSD_PRE_KEEP, 0);
+    rc = launch_fused(c, SSD_STAGE_WARMUP, SSD_PRE_KEEP, 0);
+    if (rc == SSD_OK) c->w_version += 1;
+    return rc;
 }
 
-int ssd_step(ssd_ctx *c, const void *const *const *grads)
+static int ssd_step_impl(ssd_ctx *c, const void *const *const *grads)
 {
     if (!c) return SSD_EINVAL;
     int rc = check_grads(c, grads);
@@ -653,6 +757,7 @@ int ssd_step(ssd_ctx *c, const void *const *const *grads)
     if (kind == SSD_STEP_WARMUP || kind == SSD_STEP_WARMUP_LAST) {
         rc = launch_fused(c, SSD_STAGE_WARMUP, SSD_PRE_KEEP, 0);
         if (rc != SSD_OK) return rc;
+        c->w_version += 1;
         if (kind == SSD_STEP_WARMUP_LAST) {
             // Alg. 1: w'_{t,i} = w_t for every worker -- recorded, not copied
             for (int i = 0; i < K; ++i) {
@@ -666,12 +771,21 @@ int ssd_step(ssd_ctx *c, const void *const *const *grads)
     } else {
         for (int i = 0; i < K; ++i)
             if (!c->has_local[i]) return c->fail(SSD_ESTATE, "worker %d has no local weights", i);
+        if (!c->wl_is_global && pre_action != SSD_PRE_KEEP) {
+            // pre_weight is about to take worker 0's w' for everybody (reached
+            // only after piecewise calls): all w'_i must be one global weight
+            for (int i = 0; i < K; ++i)
+                if (!c->wloc_fresh[i] || c->pulled_version[i] != c->pulled_version[0])
+                    return c->fail(SSD_ESTATE, "pre_weight is shared: every worker must have pulled the same global "
+                                               "weight since its last local update (worker %d has not)", i);
+        }
         if (c->wl_is_global && pre_action == SSD_PRE_KEEP) {
             rc = materialize(c); // only after piecewise calls moved the schedule
             if (rc != SSD_OK) return rc;
         }
         rc = launch_fused(c, SSD_STAGE_DELAY, pre_action, c->wl_is_global ? 1 : 0);
         if (rc != SSD_OK) return rc;
+        c->w_version += 1;
         // Alg. 1, Pull iteration: the updated w' were broadcast (they stay in
         // the w' arrays as w_loc) and w' = w_t from now on -- recorded only
         const bool pull = kind == SSD_STEP_DELAY_PULL;
@@ -685,7 +799,7 @@ int ssd_step(ssd_ctx *c, const void *const *const *grads)
     return SSD_OK;
 }
 
-int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const void *const *grads_i)
+static int ssd_worker_glu_update_impl(ssd_ctx *c, int32_t worker, const void *const *grads_i)
 {
     if (!c) return SSD_EINVAL;
     const int K = c->cfg.num_workers, k = c->cfg.delay_k, T = c->cfg.num_tensors;
@@ -705,6 +819,21 @@ int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const void *const *grads_i
         return c->fail(SSD_ESTATE, "worker %d is at local update %lld but the slowest worker at %lld", worker,
                        (long long)lu, (long long)dmin);
     const int pre_action = lu == 0 ? SSD_PRE_INIT : (lu % k == 0 ? SSD_PRE_REFRESH : SSD_PRE_KEEP);
+    // Alg. 2 sets pre_weight = w' here, and pre_weight is one array for all
+    // workers (Sec. 3.3: they hold the same value).  That is only the paper's
+    // pre_weight if this worker's w' is a pulled global weight, the same one
+    // for every worker of this round.
+    int64_t version = -1;
+    if (pre_action != SSD_PRE_KEEP) {
+        const bool fresh = c->wl_is_global || c->wloc_fresh[worker];
+        version = c->wl_is_global ? c->w_version : c->pulled_version[worker];
+        if (!fresh)
+            return c->fail(SSD_ESTATE, "pre_weight is shared: worker %d must pull before local update %lld "
+                                       "(its w' is not a global weight)", worker, (long long)lu);
+        if (c->pre_written > 0 && version != c->round_version)
+            return c->fail(SSD_ESTATE, "pre_weight is shared: worker %d pulled another global weight than the "
+                                       "workers before it in this round", worker);
+    }
     DeviceGuard guard(c->cfg.device);
     if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
     int rc = materialize(c);
@@ -725,6 +854,7 @@ int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const void *const *grads_i
     if (e != hipSuccess) return c->fail_hip(e, "launch of the GLU kernel");
     c->loc_update[worker] = lu + 1;
     c->wloc_fresh[worker] = 0;
+    if (pre_action != SSD_PRE_KEEP && c->pre_written == 0) c->round_version = version;
     if (pre_action != SSD_PRE_KEEP && ++c->pre_written == K) {
         c->pre_cur ^= 1; // every worker has written the same values to the other array
         c->pre_written = 0;
@@ -732,7 +862,7 @@ int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const void *const *grads_i
     return SSD_OK;
 }
 
-int ssd_worker_pull(ssd_ctx *c, int32_t worker)
+static int ssd_worker_pull_impl(ssd_ctx *c, int32_t worker)
 {
     if (!c) return SSD_EINVAL;
     const int K = c->cfg.num_workers;
@@ -747,10 +877,11 @@ int ssd_worker_pull(ssd_ctx *c, int32_t worker)
     if (e != hipSuccess) return c->fail_hip(e, "launch of the pull kernel");
     c->has_local[worker] = 1;
     c->wloc_fresh[worker] = 1;
+    c->pulled_version[worker] = c->w_version;
     return SSD_OK;
 }
 
-int ssd_set_lr(ssd_ctx *c, float lr, float lr_loc)
+static int ssd_set_lr_impl(ssd_ctx *c, float lr, float lr_loc)
 {
     if (!c) return SSD_EINVAL;
     if (c->cfg.delay_k > 0 && !(lr != 0.0f)) return c->fail(SSD_EINVAL, "lr = 0 with delay_k > 0: grad_sync divides by lr*k");
@@ -764,7 +895,7 @@ int ssd_set_lr(ssd_ctx *c, float lr, float lr_loc)
     return SSD_OK;
 }
 
-int ssd_set_tensor_multipliers(ssd_ctx *c, const float *lr_mult, const float *wd_mult)
+static int ssd_set_tensor_multipliers_impl(ssd_ctx *c, const float *lr_mult, const float *wd_mult)
 {
     if (!c) return SSD_EINVAL;
     const int T = c->cfg.num_tensors;
@@ -823,5 +954,66 @@ int ssd_get_state(ssd_ctx *c, ssd_state_view *out)
 }
 
 const char *ssd_last_error(const ssd_ctx *c) { return c ? c->err : g_init_error; }
+
+
+} // extern "C"
+
+// ---- the exported entry points: nothing throws across the C boundary -------
+namespace {
+template <typename F> int guarded(ssd_ctx *c, F f)
+{
+    try {
+        return f();
+    } catch (const std::bad_alloc &) {
+        return c ? c->fail(SSD_ENOMEM, "host allocation failed") : fail_init(SSD_ENOMEM, "host allocation failed");
+    } catch (...) {
+        return c ? c->fail(SSD_EINVAL, "unexpected C++ exception") : fail_init(SSD_EINVAL, "unexpected C++ exception");
+    }
+}
+} // namespace
+
+extern "C" {
+
+int ssd_plan_chunks(const int64_t *numel, int32_t T, int32_t chunk_elems, ssd_chunk *out, int64_t capacity,
+                    int64_t *count, int32_t *used)
+{
+    return guarded(nullptr, [&] { return ssd_plan_chunks_impl(numel, T, chunk_elems, out, capacity, count, used); });
+}
+int ssd_workspace_bytes(const ssd_config *cfg, size_t *bytes)
+{
+    return guarded(nullptr, [&] { return ssd_workspace_bytes_impl(cfg, bytes); });
+}
+int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size_t workspace_bytes, ssd_ctx **out)
+{
+    return guarded(nullptr, [&] { return ssd_init_impl(cfg, weights, workspace, workspace_bytes, out); });
+}
+int ssd_materialize(ssd_ctx *c)
+{
+    return guarded(c, [&] { return ssd_materialize_impl(c); });
+}
+int ssd_server_aggregate_update(ssd_ctx *c, const void *const *const *grads)
+{
+    return guarded(c, [&] { return ssd_server_aggregate_update_impl(c, grads); });
+}
+int ssd_step(ssd_ctx *c, const void *const *const *grads)
+{
+    return guarded(c, [&] { return ssd_step_impl(c, grads); });
+}
+int ssd_worker_glu_update(ssd_ctx *c, int32_t worker, const void *const *grads_i)
+{
+    return guarded(c, [&] { return ssd_worker_glu_update_impl(c, worker, grads_i); });
+}
+int ssd_worker_pull(ssd_ctx *c, int32_t worker)
+{
+    return guarded(c, [&] { return ssd_worker_pull_impl(c, worker); });
+}
+int ssd_set_lr(ssd_ctx *c, float lr, float lr_loc)
+{
+    return guarded(c, [&] { return ssd_set_lr_impl(c, lr, lr_loc); });
+}
+int ssd_set_tensor_multipliers(ssd_ctx *c, const float *lr_mult, const float *wd_mult)
+{
+    return guarded(c, [&] { return ssd_set_tensor_multipliers_impl(c, lr_mult, wd_mult); });
+}
 
 } // extern "C"

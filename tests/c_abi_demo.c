@@ -81,12 +81,15 @@ int main(void)
             }
     }
 
+    /* the paper's settings (Sec. 4.1, Table 1) come from the library */
     ssd_config cfg;
-    memset(&cfg, 0, sizeof cfg);
-    cfg.num_workers = K, cfg.delay_k = 2, cfg.warmup_iters = 1;
-    cfg.lr = 0.1f, cfg.momentum = 0.9f, cfg.wd = 1e-4f;
-    cfg.lr_loc = 0.4f, cfg.alpha = 2.0f, cfg.beta = 0.5f, cfg.wd_loc = 1e-4f;
-    cfg.rescale_grad = (float)(1.0 / K);
+    SSD(ssd_config_defaults(&cfg, K, 0.1f, 1e-4f));
+    if (cfg.lr_loc != 0.4f || cfg.alpha != 2.0f || cfg.beta != 0.5f || cfg.wd_loc != 1e-4f ||
+        cfg.rescale_grad != (float)(1.0 / K)) {
+        printf("ssd_config_defaults: unexpected values\n");
+        return 4;
+    }
+    cfg.delay_k = 2, cfg.warmup_iters = 1, cfg.momentum = 0.9f;
     cfg.num_tensors = T, cfg.numel = numel, cfg.device = 0, cfg.stream = NULL;
     size_t ws_bytes = 0;
     SSD(ssd_workspace_bytes(&cfg, &ws_bytes));

@@ -12,8 +12,7 @@ EXE = os.path.join(HERE, "_build", "c_abi_demo")
 
 @pytest.mark.gpu
 def test_c_program_drives_the_library():
-    if not os.path.exists(EXE):
-        pytest.skip("tests/_build/c_abi_demo is not built; run __graft_entry__.build()")
+    assert os.path.exists(EXE), "tests/_build/c_abi_demo is not built; run __graft_entry__.build()"
     print("case: C ABI demo", flush=True)
     r = subprocess.run([EXE], capture_output=True, text=True, timeout=120)
     print(r.stdout, r.stderr)

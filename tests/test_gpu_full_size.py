@@ -6,7 +6,8 @@ The path is element-wise, so the oracle can compute any element on its own:
 a seeded sample of elements of every tensor (first and last elements, both
 sides of chunk boundaries, random positions) is gathered from the inputs, run
 through the CPU oracle for the whole schedule, and compared bit for bit
-(binary32 oracle) and within 1e-5 (binary64 oracle) with the same elements of
+(binary32 oracle) and within 1e-5 per element (binary64 oracle; relative to
+the element, with a floor of a tenth of its tensor's largest value) with the same elements of
 the GPU state, after each of the last iterations so that every kernel variant
 is covered.  Properties that hold at any size are checked on whole arrays on
 the device: pre_weight equals the global weight as of the last Pull, and the
@@ -70,11 +71,13 @@ def run_full(name, piecewise_check=False, wl=None, grad_dtype=0):
     assert v.chunk_elems == 256
 
     # sample: indices into the caller's flat buffers and into the arena
-    flat_idx, arena_idx = [], []
+    flat_idx, arena_idx, seg_start, seg_len = [], [], [], []
     for t in range(T):
         idx = sample_indices(numel[t], v.chunk_elems, rng)
         if t in EXTRA_INDICES:
             idx = np.unique(np.concatenate([idx, EXTRA_INDICES[t].astype(np.int64)]))
+        seg_start.append(sum(seg_len))
+        seg_len.append(idx.size)
         flat_idx.append(idx + offs[t])
         arena_idx.append(idx + v.tensor_offset[t])
     flat_idx = torch.from_numpy(np.concatenate(flat_idx)).to(dev)
@@ -126,9 +129,12 @@ def run_full(name, piecewise_check=False, wl=None, grad_dtype=0):
         for name_, g in got.items():
             assert bit_equal(g, exp32[name_]), "%s it=%d %s: sampled elements differ from the binary32 oracle" % (
                 name, it, name_)
-            e = exp64[name_]
-            err = np.max(np.abs(g.astype(np.float64) - e)) / max(np.max(np.abs(e)), 1e-30)
-            assert err <= 1e-5, "%s it=%d %s: rel err %.3e vs binary64 oracle" % (name, it, name_, err)
+            # per element: |a-b| / max(|b|, 0.1 * max|b| over the element's tensor)
+            e = np.asarray(exp64[name_], np.float64)
+            tmax = np.maximum.reduceat(np.abs(e), seg_start)
+            floor = np.maximum(np.repeat(0.1 * tmax, seg_len), 1e-30)
+            err = np.max(np.abs(g.astype(np.float64) - e) / np.maximum(np.abs(e), floor))
+            assert err <= 1e-5, "%s it=%d %s: per-element rel err %.3e vs binary64 oracle" % (name, it, name_, err)
         # ---- whole-array properties, on the device ----
         if k > 0 and o32.d > 0 and (o32.d - 1) % k == 0 and o32.d > 1 and last_pull_w is not None:
             # pre_weight was just refreshed: it is the global weight of the previous Pull
@@ -211,8 +217,9 @@ def test_every_element_bit_exact_at_full_size(name, gd):
     from concurrent.futures import ThreadPoolExecutor
     import psutil
     from paper_2012_05396_amd import binding as B
-    if psutil.virtual_memory().available < 64 * 2 ** 30:
-        pytest.skip("needs 64 GB of free host memory for the oracle's copy of the model")
+    # a box too small for this test fails it: a skip would hide the coverage
+    assert psutil.virtual_memory().available >= 64 * 2 ** 30, \
+        "needs 64 GB of free host memory for the oracle's copy of the model"
     wl = workloads.workload(name)
     dev = torch.device("cuda", 0)
     numel = workloads.numels(wl.tensors)
@@ -286,8 +293,7 @@ def test_tensor_larger_than_2_to_31_elements():
     plus a small second tensor behind it in the arena."""
     big = 2 ** 31 + 1029
     free, _ = torch.cuda.mem_get_info()
-    if free < 80 * 2 ** 30:
-        pytest.skip("needs 80 GB of free device memory")
+    assert free >= 80 * 2 ** 30, "needs 80 GB of free device memory (a skip would hide the 64-bit offsets)"
     tensors = [workloads.TensorSpec("big.weight", (big,), "fc", 4096),
                workloads.TensorSpec("tail.bias", (77,), "bias", 4096)]
     wl = workloads._wl("big", tensors, 1, 2, 4, seed=777)

@@ -208,3 +208,54 @@ def test_multipliers_reject_null_context():
     assert B.lib.ssd_set_tensor_multipliers(None, None, None) == B.SSD_EINVAL
     assert B.lib.ssd_set_stream(None, None) == B.SSD_EINVAL
     assert B.lib.ssd_materialize(None) == B.SSD_EINVAL
+
+
+# ---- occupancy cap (LDS slice per single-wave workgroup) -----------------------
+@pytest.mark.parametrize("lds", [163840, 65536])
+def test_lds_slice_yields_the_wave_count_it_names(lds):
+    """waves * slice must fit the compute unit's LDS and one more wave must
+    not: the cap means the count it names (LDS comes in 128 granules, so 13
+    and 15 waves are not expressible and give 14 and 16)."""
+    granule = lds // 128
+    for n in range(1, 17):
+        s = B.ssd_lds_slice_bytes(n, lds)
+        assert s > 0 and s % granule == 0
+        resident = lds // s
+        assert resident == {13: 14, 15: 16}.get(n, n), (n, s, resident)
+    assert B.ssd_lds_slice_bytes(0, lds) == 0 and B.ssd_lds_slice_bytes(32, lds) == 0
+    for bad in [(-1, lds), (4, 0), (4, 1000)]:
+        with pytest.raises(B.SsdError):
+            B.ssd_lds_slice_bytes(*bad)
+
+
+# ---- the paper's settings come from the library (Sec. 4.1, Table 1) -----------
+def test_config_defaults_follow_the_papers_settings():
+    import numpy as np
+    vals = {}
+    pairs = []
+    for line in open(os.path.join(ROOT, "tests", "golden", "hyperparameters.txt")):
+        f = line.split()
+        if not f or f[0].startswith("#"):
+            continue
+        if f[0] == "lr":
+            pairs.append((float(f[1]), float(f[3])))
+        else:
+            vals[f[0]] = float(f[1])
+    assert len(pairs) == 2
+    for lr, loc_lr in pairs:
+        for K in (1, 3, 4, 16):
+            c = B.ssd_config_defaults(K, lr, 1e-4)
+            assert c.alpha == vals["alpha"] and c.beta == vals["beta"]
+            assert c.lr_loc == np.float32(loc_lr) and c.lr == np.float32(lr)
+            assert c.rescale_grad == np.float32(1.0 / K)       # Table 1: averaged gradient
+            assert c.wd == np.float32(1e-4) and c.wd_loc == c.wd
+            assert (c.num_workers, c.delay_k, c.warmup_iters, c.grad_dtype, c.chunk_elems) == (K, 0, 0, 0, 0)
+    for badK in (0, 17):
+        with pytest.raises(B.SsdError):
+            B.ssd_config_defaults(badK, 0.1, 0.0)
+    assert B.lib.ssd_config_defaults(None, 4, 0.1, 0.0) == B.SSD_EINVAL
+    # make_config is that struct plus the caller's overrides, nothing computed in Python
+    m = B.make_config([10], 4, 2, 1, 0.4, 0.9, 1e-4)
+    assert (m.lr_loc, m.alpha, m.beta, m.rescale_grad) == (np.float32(1.6), 2.0, 0.5, 0.25)
+    m = B.make_config([10], 4, 2, 1, 0.4, 0.9, 1e-4, lr_loc=1.0, alpha=1.0, beta=0.0, wd_loc=0.0, rescale_grad=1.0)
+    assert (m.lr_loc, m.alpha, m.beta, m.wd_loc, m.rescale_grad) == (1.0, 1.0, 0.0, 0.0, 1.0)

@@ -215,10 +215,16 @@ def test_brute_force_exact_dyadic():
                                w0s=[1.0, -0.5, 0.75], mode="f32", exact=True)
     _check_against_brute_force(hp, K=4, k=4, wp=3, steps=10, g_of=g_of,
                                w0s=[1.0, -0.5, 0.75], mode="f64", exact=True)
+    # no warm-up stage at all (W = 0, i.e. wp = -1): the steps-delay loop of
+    # Alg. 1 starts at iteration 0 with every w'_i = w_0 and pre_weight = w_0
+    _check_against_brute_force(hp, K=2, k=2, wp=-1, steps=6, g_of=g_of,
+                               w0s=[1.0, -0.5, 0.75], mode="f64", exact=True)
+    _check_against_brute_force(hp, K=2, k=2, wp=-1, steps=4, g_of=g_of,
+                               w0s=[1.0, -0.5, 0.75], mode="f32", exact=True)
 
 
 @pytest.mark.parametrize("mode", ["f64", "f32"])
-@pytest.mark.parametrize("K,k,wp", [(2, 2, 1), (3, 4, 3), (4, 1, 0), (5, 5, 4)])
+@pytest.mark.parametrize("K,k,wp", [(2, 2, 1), (3, 4, 3), (4, 1, 0), (5, 5, 4), (3, 3, -1), (2, 1, -1)])
 def test_brute_force_general(mode, K, k, wp):
     hp = (0.1, 0.9, 1e-4, 0.4, 2.0, 0.5, 1e-4)
     rng = np.random.default_rng(7)
@@ -309,7 +315,7 @@ def test_grad_sync_closed_form_and_limit(k):
     np.testing.assert_allclose(gs[0], exp, rtol=1e-12, atol=1e-15)
     np.testing.assert_allclose(gs[1], exp, rtol=1e-12, atol=1e-15)
 
-    # long warm-up: grad_sync -> g (Sec. 3.2.1, "after hundreds of iterations")
+    # long warm-up: grad_sync -> g (Sec. 3.2.1, the limit m^t -> 0)
     W = 400
     o = Oracle(np.array([1.0, 2.0, -1.0], np.float32), K=2, k=k, W=W, lr=lr,
                m=m, wd=0.0, lr_loc=1.0, alpha=0.0, beta=1.0, wd_loc=0.0,
