@@ -270,6 +270,42 @@ const char *ssd_last_error(const ssd_ctx *ctx);
  * caller's to free afterwards.  NULL is allowed. */
 void ssd_destroy(ssd_ctx *ctx);
 
+/* ---- for callers that cannot allocate ----------------------------------- */
+
+/* The server side of one iteration -- the same rule, rounding sequence and
+ * multi-tensor launch as ssd_server_aggregate_update -- for callers that
+ * cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  There is no context and no workspace: the
+ * call allocates nothing on the host or the device, calls no hipMalloc /
+ * hipFree and no allocating library routine.  The tables its launch needs sit
+ * in a static device array inside the library, 2,260,992 bytes per GPU
+ * (163,840 of tensor records + 2,097,152 of block table), held by every GPU
+ * the library runs on until the process ends.  Hence the limits: at most
+ * SSD_NOALLOC_MAX_TENSORS tensors and SSD_NOALLOC_MAX_BLOCKS blocks of 256
+ * elements (a tensor of n elements takes ceil(n / 256) blocks; 268,435,456
+ * elements if all are multiples of 256); a larger model is SSD_EINVAL.
+ *   numel     host [T], elements per tensor, each >= 1
+ *   weights   host [T] of device pointers, w_t, updated in place
+ *   momentum  host [T] of device pointers, the servers' momentum, updated in
+ *             place; the caller owns it (zero it before the first iteration)
+ *   grads     host [K][T] of device pointers, binary32 gradients, read-only
+ *   lr, m, wd, rescale_grad  as in ssd_config
+ * All device pointers 4-byte aligned (SSD_EALIGN); tensors whose pointers are
+ * all 16-byte aligned take 128-bit accesses.  Enqueues a few small launches
+ * that write the tables and one update launch on `stream` and returns without
+ * waiting.  Every call on a GPU uses that GPU's one static array and
+ * overwrites what the call before left there (nothing in it needs clearing:
+ * a call writes every entry it reads): calls on one stream follow each other
+ * correctly, calls that overlap on one GPU -- other streams, other host
+ * threads -- race.  Errors as everywhere: checked before anything is
+ * enqueued; message from ssd_last_error(NULL). */
+#define SSD_NOALLOC_MAX_TENSORS 1024
+#define SSD_NOALLOC_MAX_BLOCKS 1048576
+int ssd_server_aggregate_update_noalloc(int32_t num_workers, int32_t num_tensors, const int64_t *numel,
+                                        float *const *weights, float *const *momentum,
+                                        const float *const *const *grads, float lr, float m, float wd,
+                                        float rescale_grad, int32_t device, void *stream);
+
 /* ---- host-only helpers (no GPU), used by the calls above ---------------- */
 
 /* Kind of iteration number `iteration` (0-based) and pre_weight action, for

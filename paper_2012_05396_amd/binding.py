@@ -12,6 +12,7 @@ LIB_PATH = os.environ.get("SSD_LIB_PATH") or os.path.join(_HERE, "libssd.so")
 
 SSD_OK, SSD_EINVAL, SSD_EALIGN, SSD_ENOMEM, SSD_EHIP, SSD_ESTATE = 0, -1, -2, -3, -4, -5
 SSD_MAX_WORKERS = 16
+SSD_NOALLOC_MAX_TENSORS, SSD_NOALLOC_MAX_BLOCKS = 1024, 1048576
 SSD_STEP_WARMUP, SSD_STEP_WARMUP_LAST, SSD_STEP_DELAY, SSD_STEP_DELAY_PULL = 0, 1, 2, 3
 SSD_PRE_KEEP, SSD_PRE_INIT, SSD_PRE_REFRESH = 0, 1, 2
 SSD_W_LOC_IS_GLOBAL, SSD_W_LOC_IN_W_LOCAL, SSD_W_LOC_SEPARATE = 0, 1, 2
@@ -66,6 +67,9 @@ def _load():
         "ssd_worker_glu_update": (C.c_int, [C.c_void_p, C.c_int32, P(C.c_void_p)]),
         "ssd_worker_pull": (C.c_int, [C.c_void_p, C.c_int32]),
         "ssd_step": (C.c_int, [C.c_void_p, P(C.c_void_p)]),
+        "ssd_server_aggregate_update_noalloc": (C.c_int, [C.c_int32, C.c_int32, P(C.c_int64), P(C.c_void_p),
+                                                          P(C.c_void_p), P(C.c_void_p), C.c_float, C.c_float,
+                                                          C.c_float, C.c_float, C.c_int32, C.c_void_p]),
         "ssd_materialize": (C.c_int, [C.c_void_p]),
         "ssd_set_lr": (C.c_int, [C.c_void_p, C.c_float, C.c_float]),
         "ssd_set_stream": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -170,6 +174,26 @@ def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=None, beta=
     cfg.grad_sync_exact, cfg.grad_dtype = grad_sync_exact, grad_dtype
     cfg._keep = arr
     return cfg
+
+
+def ssd_server_aggregate_update_noalloc(weights, momentum, grads, lr, m, wd, rescale_grad, device=0,
+                                        stream=None):
+    """Marshal torch tensors into ssd_server_aggregate_update_noalloc:
+    weights, momentum: lists of T float32 device tensors (updated in place);
+    grads: K lists of T float32 device tensors."""
+    T, K = len(weights), len(grads)
+    for t in range(T):
+        n = weights[t].numel()
+        for x in [weights[t], momentum[t]] + [g[t] for g in grads]:
+            if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.numel() == n):
+                raise SsdError(SSD_EINVAL, "tensor %d: contiguous float32 device tensors of equal size expected" % t)
+    numel = (C.c_int64 * T)(*[w.numel() for w in weights])
+    wp = (C.c_void_p * T)(*[w.data_ptr() for w in weights])
+    mp = (C.c_void_p * T)(*[x.data_ptr() for x in momentum])
+    table = GradTable(grads)
+    _check(lib.ssd_server_aggregate_update_noalloc(
+        K, T, numel, wp, mp, table.table, lr, m, wd, rescale_grad, device,
+        stream if stream is not None else torch.cuda.current_stream().cuda_stream))
 
 
 def ssd_workspace_bytes(cfg):

@@ -52,6 +52,8 @@ def build(jobs=None, verbose=False, defines=(), lib=None, obj_dir=None):
                           ["-DSSD_K=%d" % k, "-DSSD_GD=%d" % gd]))
     units.append((os.path.join(CSRC, "ssd_aux.hip"),
                   os.path.join(OBJ, "ssd_aux.o"), []))
+    units.append((os.path.join(CSRC, "ssd_noalloc.hip"),
+                  os.path.join(OBJ, "ssd_noalloc.o"), []))
     units.append((os.path.join(CSRC, "ssd_host.hip"),
                   os.path.join(OBJ, "ssd_host.o"), []))
 
