@@ -107,6 +107,23 @@ def run_workload(torch, B, workloads, name, args, steps, warmup, P, overrides=Tr
     weights = workloads.views(wflat, wl.tensors, offs)
     gsets = [workloads.gradient_set(wl, p, device=dev, skew=args.grad_skew_elems if overrides else 0,
                                     dtype=B.GRAD_TORCH_DTYPE[gd]) for p in range(P)]
+    if overrides and args.grad_spacing_mib > 0:
+        # the same values, moved into one allocation at a fixed spacing
+        unit = args.grad_spacing_mib << 20
+        nbytes = gsets[0][0].numel() * gsets[0][0].element_size()
+        step = -(-nbytes // unit) * unit
+        pool = torch.empty(step * P * K + unit, dtype=torch.uint8, device=dev)
+        base = (-pool.data_ptr()) % unit
+        placed = []
+        for p in range(P):
+            row = []
+            for i in range(K):
+                o = base + (p * K + i) * step
+                v = pool[o:o + nbytes].view(gsets[p][i].dtype)
+                v.copy_(gsets[p][i])
+                row.append(v)
+            placed.append(row)
+        gsets = placed
     gviews = [[workloads.views(g, wl.tensors, offs) for g in gs] for gs in gsets]
     tables = [B.GradTable(g) for g in gviews]
 
@@ -263,6 +280,9 @@ def main():
                     help="time the headline workload only")
     ap.add_argument("--grad-skew-elems", type=int, default=0,
                     help="worker i's gradient buffer starts i*skew elements into its allocation")
+    ap.add_argument("--grad-spacing-mib", type=int, default=0,
+                    help="place all gradient buffers in one allocation, consecutive buffers a multiple of "
+                         "this many MiB apart (0: one allocation per buffer, as a framework would hand them over)")
     ap.add_argument("--cpu-sample-elems", type=int, default=64 * 1024 * 1024)
     ap.add_argument("--graph", action="store_true",
                     help="also time the same steps as replays of a HIP graph holding whole k-cycles")
@@ -284,7 +304,7 @@ def main():
     props = torch.cuda.get_device_properties(dev)
     P = args.pool
     overridden = bool(args.workers > 0 or args.delay >= 0 or args.chunk_elems or args.waves_per_cu or
-                      args.unfused or args.grad_skew_elems)
+                      args.unfused or args.grad_skew_elems or args.grad_spacing_mib)
 
     r = run_workload(torch, B, workloads, args.workload, args, args.steps, args.warmup, P)
     wl, N, T, K, k, W, gd, gb = (r[x] for x in ("wl", "N", "T", "K", "k", "W", "gd", "gb"))

@@ -637,14 +637,20 @@ static int check_grads(ssd_ctx *c, const void *const *const *grads)
 // Resident waves per compute unit that gave the highest HBM throughput when
 // measured on MI355X: sweeps over 2..16 waves for K = 1, 2, 4, 8 on 133-138 M-
 // element models and K = 16 on a 60 M-element one, with binary32 and with
-// bfloat16 gradient buffers.  The best cap falls as a wave carries more
-// streams, roughly as budget / (loads per lane), and is flat within +-1:
+// bfloat16 gradient buffers.  Up to K = 8 (a wave requests its whole tile at
+// once) the best cap falls as a wave carries more streams, roughly as
+// budget / (loads per lane), and is flat within +-1:
 //   plain delay kernel   58 / (2K + 3), at least 4   (K = 8: 4, K = 2: 8)
 //   from-global kernel   44 / (K + 3),  at least 4   (50 with 16-bit gradients)
 //   warm-up kernel       58 / (K + 2),  at least 6   (read-dominated: its
 //                        16-bit gradient loads count half, budget 52)
+// Beyond K = 8 a wave takes the workers in groups of 4, two groups requested
+// at a time, so its loads in flight no longer grow with K; measured at K = 16:
+// 4 waves for the plain kernel, 6 for the from-global and the warm-up kernel
+// (which have no local weights to read, so half the loads in flight).
 static int default_waves_per_cu(int K, int stage, int from_global, bool grad16)
 {
+    if (K > 8) return (stage == SSD_STAGE_WARMUP || from_global) ? 6 : 4;
     int loads2, budget, floor_n; // loads per lane in halves of a 128-bit load
     if (stage == SSD_STAGE_WARMUP)
         loads2 = (grad16 ? K : 2 * K) + 4, budget = grad16 ? 52 : 58, floor_n = 6;
