@@ -40,6 +40,9 @@ PROFILE_OF = {
 # steps each gets (whole k-cycles)
 OTHER_CONFIGS = (("resnet20", 200), ("resnet56", 200), ("resnet50", 40), ("resnet152_k2", 20),
                  ("resnet152_k4", 20), ("resnet152_k8", 24))
+# two more workloads shaped like the communication-heavy models of the paper's
+# Sec. 4.5 (AlexNet, VGG-11; K = 4 workers, 5-step delay as in Fig. 7)
+EXTRA_CONFIGS = (("alexnet", 40), ("vgg11", 20))
 # a model whose whole resident state fits the 256 MB last-level cache is bound
 # by launch latency, not by HBM: no roofline fraction is quoted for it
 CACHE_BYTES = 256 * 2 ** 20
@@ -454,6 +457,14 @@ def main():
             torch.cuda.empty_cache()
         lines.insert(3, headline_line)
         out["all_configs"] = lines
+        extra = []
+        for name, nsteps in EXTRA_CONFIGS:
+            q = run_workload(torch, B, workloads, name, args, nsteps, 10, P, overrides=False)
+            q["ctx"].close()
+            extra.append(config_line(B, q))
+            del q
+            torch.cuda.empty_cache()
+        out["extra_configs_sec_4_5_models"] = extra
     print(json.dumps(out))
 
 
