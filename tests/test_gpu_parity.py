@@ -32,6 +32,28 @@ def test_misaligned_pointers_take_scalar_path(w_shift, g_shift):
     run_schedule(ODD, K=3, k=2, W=1, steps=6, w_shift=w_shift, g_shift=g_shift, seed=5)
 
 
+@pytest.mark.parametrize("K,w_shift,g_shift", [(9, 0, 1), (11, 1, 2), (16, 3, 0), (16, 0, 0)])
+def test_grouped_kernels_on_the_scalar_path_and_large_chunks(K, w_shift, g_shift):
+    """K > 8: the wave takes the workers in groups (the last group partial for
+    K = 9, 11).  Misaligned caller pointers send every lane element by element
+    through all groups; chunks of several tiles loop over the groups per tile;
+    the exact-w_minus variant is its own kernel."""
+    print("case: groups K=%d w_shift=%d g_shift=%d" % (K, w_shift, g_shift), flush=True)
+    run_schedule(ODD, K=K, k=3, W=1, steps=1 + 7, w_shift=w_shift, g_shift=g_shift, seed=100 + K)
+    run_schedule([20000, 8193, 7], K=K, k=2, W=0, steps=5, chunk_elems=1024, w_shift=w_shift, g_shift=g_shift,
+                 seed=200 + K, hp=dict(lr=0.1, momentum=0.9, wd=1e-4, grad_sync_exact=1))
+
+
+def test_many_tiny_tensors():
+    """2000 tensors of 1 .. 300 elements with K = 16 workers: one block and one
+    table record per tensor, 38 000 pointers per gradient set."""
+    print("case: many tiny tensors", flush=True)
+    rng = np.random.default_rng(5)
+    sizes = [int(x) for x in rng.integers(1, 301, size=2000)]
+    run_schedule(sizes, K=16, k=2, W=1, steps=6, seed=6, P=2, check_every=3)
+    run_schedule(sizes[:500], K=3, k=4, W=2, steps=8, seed=7, P=2, check_every=4)
+
+
 @pytest.mark.parametrize("K", [6, 7, 9, 10, 11, 12, 13, 14, 15])
 def test_remaining_worker_counts(K):
     print("case: K=%d" % K, flush=True)

@@ -68,6 +68,21 @@ def test_noalloc_server_update_equals_the_context_entry_point():
     _run_case([300 + 7 * t for t in range(60)], K=16, iters=1, seed=5)
 
 
+@pytest.mark.gpu
+def test_noalloc_randomized_cases():
+    """Seeded random shapes, worker counts, alignments and hyper-parameters,
+    one after the other on the same static array."""
+    print("case: no-alloc entry point, randomized", flush=True)
+    rng = np.random.default_rng(2024)
+    for case in range(8):
+        T = int(rng.integers(1, 40))
+        sizes = [int(x) for x in rng.integers(1, 6000, size=T)]
+        K = int(rng.integers(1, 17))
+        hp = (float(rng.choice([0.05, 0.1, 1.0])), float(rng.choice([0.0, 0.5, 0.9])), float(rng.choice([0.0, 1e-4, 1e-2])))
+        _run_case(sizes, K=K, iters=2, seed=50 + case, w_shift=int(rng.integers(0, 4)),
+                  g_shift=int(rng.integers(0, 4)), hp=hp)
+
+
 def _args(K=2, T=2, numel=(10, 20)):
     n = (C.c_int64 * T)(*numel)
     w = (C.c_void_p * T)(*[0x10000 * (t + 1) for t in range(T)])
