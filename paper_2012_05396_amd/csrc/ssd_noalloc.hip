@@ -190,7 +190,7 @@ extern "C" int ssd_server_aggregate_update_noalloc(int32_t K, int32_t T, const i
     // records, a launch-full at a time
     const int rw = kRecHead + K;
     const int per_launch = kPutWords / rw; // whole records per launch (>= 22)
-    put_payload p;
+    put_payload p = {}; // the whole struct travels with each launch
     int64_t first_block = 0;
     for (int t0 = 0; t0 < T; t0 += per_launch) {
         const int nt = T - t0 < per_launch ? T - t0 : per_launch;
