@@ -209,10 +209,12 @@ def test_full_size_sampled_parity_16bit_gradients(name, gd):
     run_full(name, grad_dtype=gd, piecewise_check=(name == "resnet50"))
 
 
-@pytest.mark.parametrize("name,gd", [("vgg16", 0), ("resnet152_k4", 0), ("vgg16", 1)])
+@pytest.mark.parametrize("name,gd", [("vgg16", 0), ("resnet152_k4", 0), ("vgg16", 1), ("resnet50", 0),
+                                     ("resnet152_k8", 0), ("resnet152_k2", 1)])
 def test_every_element_bit_exact_at_full_size(name, gd):
     """The 138 M-element benchmark configuration (also with bfloat16 gradient
-    buffers) and the K = 16 one, every element of every array:
+    buffers), the 25.6 M-element one and the K = 16 one at three delays (one of
+    them with bfloat16 gradients), every element of every array:
     the binary32 oracle runs on all host threads (one contiguous element range
     each -- the rules are element-wise) through warm-up, the first local
     update, a Pull and the refresh after it, and the whole GPU state is
