@@ -106,9 +106,10 @@ def run_workload(torch, B, workloads, name, args, steps, warmup, P, overrides=Tr
     N, T, K, k, W = sum(numel), len(numel), wl.K, wl.k, wl.W
     gd = {"f32": B.SSD_GRAD_F32, "bf16": B.SSD_GRAD_BF16, "f16": B.SSD_GRAD_F16}[args.grad_dtype if overrides else "f32"]
     gb = 4 if gd == B.SSD_GRAD_F32 else 2
-    wflat, offs = workloads.initial_weights(wl, device=dev)
+    align = args.tensor_align_elems if overrides else 64
+    wflat, offs = workloads.initial_weights(wl, device=dev, align=align)
     weights = workloads.views(wflat, wl.tensors, offs)
-    gsets = [workloads.gradient_set(wl, p, device=dev, skew=args.grad_skew_elems if overrides else 0,
+    gsets = [workloads.gradient_set(wl, p, device=dev, align=align, skew=args.grad_skew_elems if overrides else 0,
                                     dtype=B.GRAD_TORCH_DTYPE[gd]) for p in range(P)]
     if overrides and args.grad_spacing_mib > 0:
         # the same values, moved into one allocation at a fixed spacing
@@ -283,6 +284,9 @@ def main():
                     help="time the headline workload only")
     ap.add_argument("--grad-skew-elems", type=int, default=0,
                     help="worker i's gradient buffer starts i*skew elements into its allocation")
+    ap.add_argument("--tensor-align-elems", type=int, default=64,
+                    help="alignment, in elements, of each tensor's start inside the flat weight and gradient "
+                         "buffers of the synthetic workload (64 elements = 256 bytes)")
     ap.add_argument("--grad-spacing-mib", type=int, default=0,
                     help="place all gradient buffers in one allocation, consecutive buffers a multiple of "
                          "this many MiB apart (0: one allocation per buffer, as a framework would hand them over)")
@@ -307,7 +311,8 @@ def main():
     props = torch.cuda.get_device_properties(dev)
     P = args.pool
     overridden = bool(args.workers > 0 or args.delay >= 0 or args.chunk_elems or args.waves_per_cu or
-                      args.unfused or args.grad_skew_elems or args.grad_spacing_mib)
+                      args.unfused or args.grad_skew_elems or args.grad_spacing_mib or
+                      args.tensor_align_elems != 64)
 
     r = run_workload(torch, B, workloads, args.workload, args, args.steps, args.warmup, P)
     wl, N, T, K, k, W, gd, gb = (r[x] for x in ("wl", "N", "T", "K", "k", "W", "gd", "gb"))

@@ -161,7 +161,11 @@ int ssd_workspace_bytes(const ssd_config *cfg, size_t *bytes);
  * num = 0; momentum starts at 0).
  *   weights   host [T] of device pointers: the global weights w_t, owned by
  *             the caller, updated in place by every server update; must stay
- *             valid until ssd_destroy.
+ *             valid until ssd_destroy.  (Any 4-byte alignment works and 16
+ *             bytes select the 128-bit path; tensors that start at multiples
+ *             of 1 KiB, weights and gradients alike, measured 1-5 % faster
+ *             on models of hundreds of tensors: a wave's 256-element tile of
+ *             the caller's arrays is then one aligned 1 KiB piece.)
  *   workspace device memory of at least ssd_workspace_bytes, 256-byte
  *             aligned, owned by the caller, used exclusively by the context
  *             until ssd_destroy.
