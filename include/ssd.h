@@ -118,7 +118,12 @@ typedef struct {
 
 /* Device-side state, for inspection.  All arrays are "arena" arrays of
  * arena_elems floats in which tensor t occupies
- * [tensor_offset[t], tensor_offset[t] + numel[t]).  Worker i's copy of a
+ * [tensor_offset[t], tensor_offset[t] + numel[t]).  Tensors own whole blocks
+ * of chunk_elems elements, in tensor order; a tensor of at least 8192 elements
+ * whose weight pointer is 16-byte aligned does not start at the beginning of
+ * its first block but ((address mod 1024) / 4) elements into it, so that the
+ * 256-element tiles the kernels work on are aligned 1 KiB pieces of the
+ * caller's arrays as well as of these.  Worker i's copy of a
  * per-worker array starts at base + i * arena_elems.  The pointers stay valid
  * until ssd_destroy; the data they show are those of the work enqueued so
  * far (synchronise the stream before reading). */
@@ -161,11 +166,13 @@ int ssd_workspace_bytes(const ssd_config *cfg, size_t *bytes);
  * num = 0; momentum starts at 0).
  *   weights   host [T] of device pointers: the global weights w_t, owned by
  *             the caller, updated in place by every server update; must stay
- *             valid until ssd_destroy.  (Any 4-byte alignment works and 16
- *             bytes select the 128-bit path; tensors that start at multiples
- *             of 1 KiB, weights and gradients alike, measured 1-5 % faster
- *             on models of hundreds of tensors: a wave's 256-element tile of
- *             the caller's arrays is then one aligned 1 KiB piece.)
+ *             valid until ssd_destroy.  Any 4-byte alignment works; 16 bytes
+ *             (for the weight and every gradient pointer of a tensor) select
+ *             the 128-bit path.  Tensors need not start at 1 KiB boundaries
+ *             for full speed: the state arrays are laid out to follow the
+ *             weight pointers' 1 KiB grid (see ssd_state_view), which pays
+ *             off when the gradient buffers share that phase, as buffers laid
+ *             out like the weights do.
  *   workspace device memory of at least ssd_workspace_bytes, 256-byte
  *             aligned, owned by the caller, used exclusively by the context
  *             until ssd_destroy.

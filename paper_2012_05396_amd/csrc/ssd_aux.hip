@@ -34,16 +34,18 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_glu_kernel(const ssd_glu_args a
     gfloat *wlp = ssd_global(a.wl) + blk.ao;
     cgfloat *presrc = ssd_global(a.pre_src) + blk.ao;
     gfloat *predst = ssd_global(a.pre_dst) + blk.ao;
-    const unsigned len = blk.len, tid = threadIdx.x;
+    const unsigned lo = blk.lo, len = blk.len, tid = threadIdx.x;
     const ssd_hyper h = ssd_hyper_of(a.h, a.thyper[blk.tensor]);
     if (vec) {
-        const unsigned len4 = len & ~3u;
-        for (unsigned e = tid * 4; e < len4; e += SSD_BLOCK * 4)
+        // whole vectors from the lead-in (a multiple of 4 elements, see
+        // ssd_tensor_desc) to the last whole vector, then the tail
+        const unsigned len4 = lo + ((len - lo) & ~3u);
+        for (unsigned e = lo + tid * 4; e < len4; e += SSD_BLOCK * 4)
             ssd_glu_elems<PRE, GD, 4>(h, gp, wlp, presrc, predst, e);
         const unsigned e = len4 + tid;
         if (e < len) ssd_glu_elems<PRE, GD, 1>(h, gp, wlp, presrc, predst, e);
     } else {
-        for (unsigned e = tid; e < len; e += SSD_BLOCK)
+        for (unsigned e = lo + tid; e < len; e += SSD_BLOCK)
             ssd_glu_elems<PRE, GD, 1>(h, gp, wlp, presrc, predst, e);
     }
 }
@@ -95,15 +97,15 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_pull_kernel(const ssd_pull_args
     const bool vec = ssd_aligned16(td.w);
     cgfloat *wp = ssd_global((const float *)td.w) + blk.off;
     gfloat *wlp = ssd_global(a.wl) + blk.ao, *wlocp = ssd_global(a.wloc) + blk.ao;
-    const unsigned len = blk.len, tid = threadIdx.x;
+    const unsigned lo = blk.lo, len = blk.len, tid = threadIdx.x;
     if (vec) {
-        const unsigned len4 = len & ~3u;
-        for (unsigned e = tid * 4; e < len4; e += SSD_BLOCK * 4)
+        const unsigned len4 = lo + ((len - lo) & ~3u);
+        for (unsigned e = lo + tid * 4; e < len4; e += SSD_BLOCK * 4)
             ssd_pull_elems<INIT, 4>(wp, wlp, wlocp, e);
         const unsigned e = len4 + tid;
         if (e < len) ssd_pull_elems<INIT, 1>(wp, wlp, wlocp, e);
     } else {
-        for (unsigned e = tid; e < len; e += SSD_BLOCK) ssd_pull_elems<INIT, 1>(wp, wlp, wlocp, e);
+        for (unsigned e = lo + tid; e < len; e += SSD_BLOCK) ssd_pull_elems<INIT, 1>(wp, wlp, wlocp, e);
     }
 }
 

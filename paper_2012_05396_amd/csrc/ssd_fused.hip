@@ -164,21 +164,23 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
     }
 }
 
-// One 256-element tile: lane l owns elements e0 .. e0+3 (e0 = base + 4l).
-// Full vectors take the 128-bit path; a lane at the ragged end of the block,
-// or any lane when a caller pointer is not 16-byte aligned, goes element by
-// element -- in both cases with the head state preloaded in `s`.
+// One 256-element tile: lane l owns elements e0 .. e0+3 (e0 = base + 4l);
+// elements lo .. len-1 of the block belong to the tensor.  Full vectors take
+// the 128-bit path; a lane at a ragged end of the block, or any lane when a
+// caller pointer is not 16-byte aligned, goes element by element -- in both
+// cases with the head state preloaded in `s`.
 template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF>
 __device__ __forceinline__ void ssd_tile(const ssd_hyper &h, const typename ssd_gvec<GD, 4>::ptr (&gp)[K],
                                          gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t A,
-                                         unsigned e0, unsigned len, bool vec, const ssd_head_regs<G, 4> &s)
+                                         unsigned e0, unsigned lo, unsigned len, bool vec,
+                                         const ssd_head_regs<G, 4> &s)
 {
-    if (vec && e0 + 3 < len) {
+    if (vec && e0 >= lo && e0 + 3 < len) {
         ssd_finish<K, GD, STAGE, PRE, FG, XW, G, PF, 4>(h, gp, wp, momp, prep, wlp, A, e0, s);
-    } else if (e0 < len) {
+    } else if (e0 + 3 >= lo && e0 < len) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            if (e0 + v < len) {
+            if (e0 + v >= lo && e0 + v < len) {
                 ssd_head_regs<G, 1> s1;
                 s1.mo[0] = s.mo[v];
                 s1.p[0] = s.p[v];
@@ -212,14 +214,14 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
     ssd_head_regs<G, 4> s;
     ssd_load_head<K, STAGE, PRE, FG, G, 4>(momp, prep, wlp, A, lane * 4, s);
 
-    // block -> tensor -> one record {w, first_block, numel, g_0 .. g_{K-1}}
+    // block -> tensor -> one record {w, elem0, numel, g_0 .. g_{K-1}}
     // and the tensor's hyper-parameters
     const ssd_hyper h = ssd_hyper_of(hglobal, thyper[t]);
     const int64_t *rec = rec_table + (int64_t)t * (K + 3);
     float *w = reinterpret_cast<float *>(rec[0]);
-    const int64_t off = ((int64_t)blockIdx.x - rec[1]) * C;
-    const int64_t left = rec[2] - off;
-    const unsigned len = left < (int64_t)C ? (unsigned)left : C;
+    int64_t off;
+    unsigned lo, len;
+    ssd_block_range((int64_t)blockIdx.x, C, rec[1], rec[2], off, lo, len);
     typedef typename ssd_gvec<GD, 4>::ptr gptr;
     gptr gp[K];
     bool vec = ssd_aligned16(w);
@@ -233,7 +235,7 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
 
     unsigned base = 0;
     for (;;) {
-        ssd_tile<K, GD, STAGE, PRE, FG, XW, G, PF>(h, gp, wp, momp, prep, wlp, A, base + lane * 4, len, vec, s);
+        ssd_tile<K, GD, STAGE, PRE, FG, XW, G, PF>(h, gp, wp, momp, prep, wlp, A, base + lane * 4, lo, len, vec, s);
         base += SSD_BLOCK * 4;
         if (base >= len) break; // uniform
         ssd_load_head<K, STAGE, PRE, FG, G, 4>(momp, prep, wlp, A, base + lane * 4, s);

@@ -174,7 +174,7 @@ struct DeviceGuard {
 struct Layout {
     int64_t A = 0;      // elements of one state array that hold tensors
     int64_t stride = 0; // elements from one state array to the next (>= A)
-    std::vector<int64_t> tensor_offset, first_block;
+    std::vector<int64_t> tensor_offset, first_block; // tensor_offset[t] = first_block[t] * chunk_elems + lead-in
     int32_t chunk_elems = 0;
     int64_t num_chunks = 0, blocks_per_xcd = 0;
     size_t off_mom = 0, off_pre0 = 0, off_pre1 = 0, off_wl = 0, off_wloc = 0;
@@ -207,21 +207,44 @@ int check_config(const ssd_config *c)
     return SSD_OK;
 }
 
-int make_layout(const ssd_config *c, Layout *L)
+// Lead-in of a tensor in its first arena block (see ssd_tensor_desc): the
+// element phase of the weight pointer inside its 1 KiB line, so that the
+// arena's 256-element tiles are aligned 1 KiB pieces of the caller's arrays
+// too.  Only for 16-byte aligned pointers (the lead-in is then a multiple of 4
+// elements and the 128-bit path keeps its alignment) and for tensors of at
+// least 32 tiles, where the extra block it can cost is at most 3 % of the
+// tensor's blocks.
+constexpr int64_t kLeadMinElems = 32 * 256;
+constexpr int64_t kLeadMax = 252;
+
+int64_t lead_of(const float *w, int64_t numel)
+{
+    const uintptr_t a = reinterpret_cast<uintptr_t>(w);
+    if (numel < kLeadMinElems || a % 16) return 0;
+    return (int64_t)(a % 1024) / 4;
+}
+
+// weights == nullptr: sizes for the worst case over all weight alignments
+// (what ssd_workspace_bytes reports before the pointers are known).
+int make_layout(const ssd_config *c, float *const *weights, Layout *L)
 {
     const int T = c->num_tensors, K = c->num_workers;
-    int rc = ssd_plan_chunks(c->numel, T, c->chunk_elems, nullptr, 0, &L->num_chunks, &L->chunk_elems);
+    int64_t unused = 0;
+    int rc = ssd_plan_chunks(c->numel, T, c->chunk_elems, nullptr, 0, &unused, &L->chunk_elems);
     if (rc != SSD_OK) return rc;
-    if (L->num_chunks > 0x7fffffffLL) return fail_init(SSD_EINVAL, "model needs %lld chunks, more than one launch holds", (long long)L->num_chunks);
     // arena: tensor t owns whole blocks of chunk_elems elements, in tensor order
     L->tensor_offset.resize(T);
     L->first_block.resize(T);
     int64_t blocks = 0;
     for (int t = 0; t < T; ++t) {
+        const int64_t lead = weights ? lead_of(weights[t], c->numel[t])
+                                     : (c->numel[t] >= kLeadMinElems ? kLeadMax : 0);
         L->first_block[t] = blocks;
-        L->tensor_offset[t] = blocks * L->chunk_elems;
-        blocks += (c->numel[t] + L->chunk_elems - 1) / L->chunk_elems;
+        L->tensor_offset[t] = blocks * L->chunk_elems + (weights ? lead : 0);
+        blocks += (c->numel[t] + lead + L->chunk_elems - 1) / L->chunk_elems;
     }
+    L->num_chunks = blocks;
+    if (L->num_chunks > 0x7fffffffLL) return fail_init(SSD_EINVAL, "model needs %lld chunks, more than one launch holds", (long long)L->num_chunks);
     const int64_t a = blocks * L->chunk_elems; // blocks == num_chunks
     L->A = a;
     size_t o = 0;
@@ -296,7 +319,7 @@ struct ssd_ctx {
     bool wl_is_global = false, wl_holds_wloc = false;
     int pre_cur = 0;      // which pre_weight array is current
     int pre_written = 0;  // workers that have written the other one this round
-    std::vector<int64_t> scratch; // [T][K+3] records: w, first_block, numel, g_0..g_{K-1}
+    std::vector<int64_t> scratch; // [T][K+3] records: w, arena element of element 0, numel, g_0..g_{K-1}
     char err[512];
 
     int fail(int code, const char *fmt, ...)
@@ -434,7 +457,7 @@ static int ssd_workspace_bytes_impl(const ssd_config *cfg, size_t *bytes)
     int rc = check_config(cfg);
     if (rc != SSD_OK) return rc;
     Layout L;
-    rc = make_layout(cfg, &L);
+    rc = make_layout(cfg, nullptr, &L);
     if (rc != SSD_OK) return rc;
     *bytes = L.total;
     return SSD_OK;
@@ -497,7 +520,7 @@ static int init_context(ssd_ctx *c, const ssd_config *cfg, float *const *weights
     c->cfg = *cfg;
     c->numel.assign(cfg->numel, cfg->numel + T);
     c->cfg.numel = c->numel.data();
-    rc = make_layout(&c->cfg, &c->L);
+    rc = make_layout(&c->cfg, weights, &c->L);
     if (rc != SSD_OK) {
         delete c;
         return rc;
@@ -537,7 +560,7 @@ static int init_context(ssd_ctx *c, const ssd_config *cfg, float *const *weights
     c->scratch.resize((size_t)T * (K + 3));
     for (int t = 0; t < T; ++t) {
         c->scratch[(size_t)t * (K + 3) + 0] = (int64_t) reinterpret_cast<uintptr_t>(weights[t]);
-        c->scratch[(size_t)t * (K + 3) + 1] = c->L.first_block[t];
+        c->scratch[(size_t)t * (K + 3) + 1] = c->L.tensor_offset[t];
         c->scratch[(size_t)t * (K + 3) + 2] = c->numel[t];
     }
 
@@ -589,7 +612,7 @@ static int init_context(ssd_ctx *c, const ssd_config *cfg, float *const *weights
     std::vector<ssd_tensor_desc> descs(T);
     for (int t = 0; t < T; ++t) {
         descs[t].w = weights[t];
-        descs[t].first_block = L.first_block[t];
+        descs[t].elem0 = L.tensor_offset[t];
         descs[t].numel = c->numel[t];
         const int64_t end = t + 1 < T ? L.first_block[t + 1] : L.num_chunks;
         for (int64_t b = L.first_block[t]; b < end; ++b)

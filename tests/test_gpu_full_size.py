@@ -180,8 +180,10 @@ def run_full(name, piecewise_check=False, wl=None, grad_dtype=0, tol_elem=1e-5):
             a, _ = ctx._arena(getattr(va, which), cnt)
             b, _ = ctx2._arena(getattr(vb, which), cnt)
             for t in range(T):
-                sl = slice(va.tensor_offset[t], va.tensor_offset[t] + numel[t])
-                assert torch.equal(a[:, sl].view(torch.int32), b[:, sl].view(torch.int32)), (name, which, t)
+                # each context has its own arena offsets (they follow its weight pointers)
+                sa = slice(va.tensor_offset[t], va.tensor_offset[t] + numel[t])
+                sb = slice(vb.tensor_offset[t], vb.tensor_offset[t] + numel[t])
+                assert torch.equal(a[:, sa].view(torch.int32), b[:, sb].view(torch.int32)), (name, which, t)
     ctx.close()
     if ctx2 is not None:
         ctx2.close()

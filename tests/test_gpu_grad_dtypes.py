@@ -97,6 +97,17 @@ def test_remaining_worker_counts_and_chunks(gd):
 
 
 @pytest.mark.parametrize("gd", [BF16, F16])
+@pytest.mark.parametrize("K,w_shift,g_shift", [(3, 0, 0), (12, 0, 4), (2, 4, 2)])
+def test_lead_in_of_large_tensors(gd, K, w_shift, g_shift):
+    """Tensors of 32 tiles and more start inside their first arena block (the
+    tiles follow the weight pointer's 1 KiB grid); 16-bit gradients at the
+    same element offsets, at 8-byte and at 4-byte alignment."""
+    print("case: %s lead-in K=%d w_shift=%d g_shift=%d" % (NAMES[gd], K, w_shift, g_shift), flush=True)
+    run_schedule([9000, 8192 + 3, 64, 10001, 20000, 5], K=K, k=2, W=1, steps=6, w_shift=w_shift, g_shift=g_shift,
+                 seed=40 + K, grad_dtype=gd)
+
+
+@pytest.mark.parametrize("gd", [BF16, F16])
 def test_variants_and_plain_oracle(gd):
     print("case: %s variants" % NAMES[gd], flush=True)
     hp = dict(lr=0.05, momentum=0.8, wd=1e-3, lr_loc=0.3, alpha=1.5, beta=0.25, wd_loc=2e-3,

@@ -44,6 +44,62 @@ def test_grouped_kernels_on_the_scalar_path_and_large_chunks(K, w_shift, g_shift
                  seed=200 + K, hp=dict(lr=0.1, momentum=0.9, wd=1e-4, grad_sync_exact=1))
 
 
+BIG = [9000, 8192 + 3, 64, 10001, 20000, 12345, 8192, 5]   # tensors of 32 tiles and more get a lead-in
+
+
+@pytest.mark.parametrize("K,w_shift,g_shift,chunk", [(3, 0, 0, 0), (4, 0, 4, 0), (2, 0, 1, 0), (3, 4, 0, 1024),
+                                                    (9, 0, 0, 0), (16, 8, 8, 0), (5, 1, 0, 0), (8, 0, 0, 512)])
+def test_lead_in_of_large_tensors(K, w_shift, g_shift, chunk):
+    """Tensors of at least 32 tiles start inside their first arena block so that
+    tiles follow the 1 KiB grid of the weight pointer (the harness places tensors
+    at multiples of 256 bytes plus the shift, so all four phases occur).  The
+    gradient buffers share the phase (shift equal), have another one (still
+    16-byte aligned: 128-bit path) or are not 16-byte aligned (element by
+    element, with the lead-in of the aligned weights); misaligned weights get
+    no lead-in.  Fused step, also against the piecewise calls."""
+    print("case: lead-in K=%d w_shift=%d g_shift=%d chunk=%d" % (K, w_shift, g_shift, chunk), flush=True)
+    from paper_2012_05396_amd import binding as B
+    model, _ = run_schedule(BIG, K=K, k=2, W=1, steps=6, w_shift=w_shift, g_shift=g_shift, chunk_elems=chunk,
+                            seed=300 + K)
+    # the state view reports where each tensor starts; large aligned tensors do not start on a block boundary
+    cfg = B.make_config(BIG, K, 2, 1, 0.1, 0.9, 1e-4, stream=torch.cuda.current_stream().cuda_stream,
+                        chunk_elems=chunk)
+    ctx = B.Context(cfg, model.weights)
+    v = ctx.ssd_get_state()
+    C = v.chunk_elems
+    for t, n in enumerate(BIG):
+        a = model.weights[t].data_ptr()
+        lead = (a % 1024) // 4 if (n >= 32 * 256 and a % 16 == 0) else 0
+        assert v.tensor_offset[t] % C == lead, (t, v.tensor_offset[t], lead)
+    ctx.close()
+
+
+def test_lead_in_piecewise_equals_fused():
+    print("case: lead-in, piecewise", flush=True)
+    from oracle.ssd_oracle import Oracle
+    from paper_2012_05396_amd import binding as B
+    K, k, W = 3, 2, 1
+    m = Model(BIG, K, seed=55)
+    ctx = B.Context(B.make_config(BIG, K, k, W, 0.1, 0.9, 1e-4, stream=torch.cuda.current_stream().cuda_stream),
+                    m.weights)
+    o = Oracle(m.w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=1e-4, mode="f32")
+    for it in range(W + 2 * k + 1):
+        p = it % 3
+        ctx.ssd_server_aggregate_update(m.g_dev[p])
+        if it == W - 1:
+            for i in range(K):
+                ctx.ssd_worker_pull(i)
+        elif it >= W:
+            for i in range(K):
+                ctx.ssd_worker_glu_update(i, m.g_dev[p][i])
+            if (it - W) % k == k - 1:
+                for i in range(K):
+                    ctx.ssd_worker_pull(i)
+        o.step(m.g_host[p])
+        compare_state(ctx, m, o, exact=True, where="lead-in piecewise it=%d" % it)
+    ctx.close()
+
+
 def test_many_tiny_tensors():
     """2000 tensors of 1 .. 300 elements with K = 16 workers: one block and one
     table record per tensor, 38 000 pointers per gradient set."""
