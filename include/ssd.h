@@ -363,6 +363,23 @@ int ssd_plan_chunks(const int64_t *numel, int32_t num_tensors, int32_t chunk_ele
                     ssd_chunk *out, int64_t capacity, int64_t *count,
                     int32_t *chunk_elems_used);
 
+/* The arena layout and the blocks of the launch that ssd_init would choose for
+ * this configuration and these weight pointers.  Host arithmetic on the
+ * pointer VALUES only: nothing is dereferenced and no GPU is touched.  It
+ * differs from ssd_plan_chunks by the lead-in of large tensors (see
+ * ssd_state_view): a block is chunk_elems consecutive arena elements, and the
+ * part of it that belongs to the tensor may start after the block's start.
+ *   tensor_offset  [T] or NULL: arena element of each tensor's element 0, as
+ *                  ssd_get_state reports it
+ *   out, capacity  NULL, or room for `capacity` blocks: block b covers `len`
+ *                  elements of tensor `tensor` from element `offset` on
+ *   num_blocks     NULL, or the number of blocks (workgroups of a launch)
+ *   bytes          NULL, or the workspace this layout needs; never more than
+ *                  ssd_workspace_bytes, which holds for every alignment
+ * Every element of every tensor lies in exactly one block. */
+int ssd_plan_arena(const ssd_config *cfg, float *const *weights, int64_t *tensor_offset,
+                   ssd_chunk *out, int64_t capacity, int64_t *num_blocks, size_t *bytes);
+
 /* ---- measurement aid ---------------------------------------------------- */
 
 /* Plain copy of n floats, device src -> device dst, on `stream`, with the same

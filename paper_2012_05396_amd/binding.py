@@ -81,6 +81,8 @@ def _load():
         "ssd_step_kind_of": (C.c_int, [C.c_int64, C.c_int32, C.c_int32, C.c_int64, P(C.c_int32)]),
         "ssd_plan_chunks": (C.c_int, [P(C.c_int64), C.c_int32, C.c_int32, P(ssd_chunk), C.c_int64,
                                       P(C.c_int64), P(C.c_int32)]),
+        "ssd_plan_arena": (C.c_int, [P(ssd_config), P(C.c_void_p), P(C.c_int64), P(ssd_chunk), C.c_int64,
+                                     P(C.c_int64), P(C.c_size_t)]),
     }
     for name, (res, args) in sigs.items():
         f = getattr(lib, name)
@@ -119,6 +121,21 @@ def ssd_plan_chunks(numel, chunk_elems=0):
     out = (ssd_chunk * cnt.value)()
     _check(lib.ssd_plan_chunks(arr, T, chunk_elems, out, cnt.value, C.byref(cnt), C.byref(used)))
     return [(c.tensor, c.offset, c.len) for c in out], used.value
+
+
+def ssd_plan_arena(cfg, weight_addresses):
+    """Layout of the state arrays for these weight pointers (plain integers:
+    host arithmetic only).  Returns (tensor_offset, blocks, workspace bytes),
+    blocks as (tensor, first element, count) per block of a launch."""
+    T = cfg.num_tensors
+    assert len(weight_addresses) == T
+    wp = (C.c_void_p * T)(*weight_addresses)
+    off = (C.c_int64 * T)()
+    nb, nbytes = C.c_int64(0), C.c_size_t(0)
+    _check(lib.ssd_plan_arena(C.byref(cfg), wp, off, None, 0, C.byref(nb), C.byref(nbytes)))
+    out = (ssd_chunk * nb.value)()
+    _check(lib.ssd_plan_arena(C.byref(cfg), wp, off, out, nb.value, None, None))
+    return list(off), [(c.tensor, c.offset, c.len) for c in out], nbytes.value
 
 
 def ssd_probe_copy(src, dst, stream=None):

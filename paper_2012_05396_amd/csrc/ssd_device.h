@@ -83,7 +83,7 @@ struct ssd_block {
 };
 
 // the part of block b (arena elements [b*C, b*C + C)) that belongs to a tensor
-static __device__ __forceinline__ void ssd_block_range(int64_t b, unsigned C, int64_t elem0, int64_t numel,
+static __host__ __device__ __forceinline__ void ssd_block_range(int64_t b, unsigned C, int64_t elem0, int64_t numel,
                                                        int64_t &off, unsigned &lo, unsigned &len)
 {
     off = b * C - elem0;

@@ -463,6 +463,37 @@ static int ssd_workspace_bytes_impl(const ssd_config *cfg, size_t *bytes)
     return SSD_OK;
 }
 
+static int ssd_plan_arena_impl(const ssd_config *cfg, float *const *weights, int64_t *tensor_offset,
+                               ssd_chunk *out, int64_t capacity, int64_t *num_blocks, size_t *bytes)
+{
+    int rc = check_config(cfg);
+    if (rc != SSD_OK) return rc;
+    if (!weights) return fail_init(SSD_EINVAL, "weights is NULL");
+    const int T = cfg->num_tensors;
+    for (int t = 0; t < T; ++t)
+        if (reinterpret_cast<uintptr_t>(weights[t]) % sizeof(float))
+            return fail_init(SSD_EALIGN, "weights[%d] is not 4-byte aligned", t);
+    Layout L;
+    rc = make_layout(cfg, weights, &L);
+    if (rc != SSD_OK) return rc;
+    if (tensor_offset) std::copy(L.tensor_offset.begin(), L.tensor_offset.end(), tensor_offset);
+    if (num_blocks) *num_blocks = L.num_chunks;
+    if (bytes) *bytes = L.total;
+    if (out)
+        for (int t = 0; t < T; ++t) {
+            const int64_t end = t + 1 < T ? L.first_block[t + 1] : L.num_chunks;
+            for (int64_t b = L.first_block[t]; b < end && b < capacity; ++b) {
+                int64_t off;
+                unsigned lo, len;
+                ssd_block_range(b, (unsigned)L.chunk_elems, L.tensor_offset[t], cfg->numel[t], off, lo, len);
+                out[b].tensor = t;
+                out[b].offset = off + lo;
+                out[b].len = (int32_t)(len - lo);
+            }
+        }
+    return SSD_OK;
+}
+
 void ssd_destroy(ssd_ctx *ctx)
 {
     if (!ctx) return;
@@ -1017,6 +1048,12 @@ int ssd_plan_chunks(const int64_t *numel, int32_t T, int32_t chunk_elems, ssd_ch
 int ssd_workspace_bytes(const ssd_config *cfg, size_t *bytes)
 {
     return guarded(nullptr, [&] { return ssd_workspace_bytes_impl(cfg, bytes); });
+}
+int ssd_plan_arena(const ssd_config *cfg, float *const *weights, int64_t *tensor_offset, ssd_chunk *out,
+                   int64_t capacity, int64_t *num_blocks, size_t *bytes)
+{
+    return guarded(nullptr,
+                   [&] { return ssd_plan_arena_impl(cfg, weights, tensor_offset, out, capacity, num_blocks, bytes); });
 }
 int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace, size_t workspace_bytes, ssd_ctx **out)
 {

@@ -71,6 +71,10 @@ def test_lead_in_of_large_tensors(K, w_shift, g_shift, chunk):
         a = model.weights[t].data_ptr()
         lead = (a % 1024) // 4 if (n >= 32 * 256 and a % 16 == 0) else 0
         assert v.tensor_offset[t] % C == lead, (t, v.tensor_offset[t], lead)
+    # the host-only planner names the same layout from the pointer values alone
+    off, blocks, nbytes = B.ssd_plan_arena(cfg, [w.data_ptr() for w in model.weights])
+    assert off == [v.tensor_offset[t] for t in range(len(BIG))] and len(blocks) == v.num_chunks
+    assert nbytes <= B.ssd_workspace_bytes(cfg)
     ctx.close()
 
 

@@ -67,3 +67,49 @@ def test_workspace_holds_the_state_arrays(numel, K, k, chunk, gd):
     assert n == B.ssd_workspace_bytes(B.make_config(numel, K, k, 1, 0.1, 0.9, 1e-4, chunk_elems=chunk))
     if K < 16:
         assert ws(K + 1) >= n
+
+
+# weight "pointers": any 4-byte aligned addresses (never dereferenced); mixes 1 KiB-, 256-, 16- and 4-byte phases
+addresses = st.builds(lambda base, fine, kind: base * 1024 + (fine * [1024, 256, 16, 4][kind]) % 1024,
+                      st.integers(1, 1 << 30), st.integers(0, 255), st.integers(0, 3))
+big_numel_lists = st.lists(st.one_of(st.integers(1, 9), st.integers(8180, 8200), st.integers(1, 70000)),
+                           min_size=1, max_size=10)
+
+
+@settings(**SET)
+@given(big_numel_lists, chunk_sizes, st.data())
+def test_arena_follows_the_weight_pointers_and_covers_every_element_once(numel, chunk, data):
+    """Large 16-byte aligned tensors sit in the arena at their weight pointer's
+    phase inside a 1 KiB line (so arena tiles are aligned pieces of the caller's
+    arrays); every other tensor starts its first block; tensors own disjoint
+    runs of whole blocks in order; every element lies in exactly one block; the
+    layout never needs more workspace than the size quoted without pointers."""
+    addr = [data.draw(addresses) for _ in numel]
+    cfg = B.make_config(numel, 3, 2, 1, 0.1, 0.9, 1e-4, chunk_elems=chunk)
+    off, blocks, nbytes = B.ssd_plan_arena(cfg, addr)
+    c = chunk or 256
+    assert nbytes <= B.ssd_workspace_bytes(cfg)
+    end_prev = 0
+    for t, n in enumerate(numel):
+        lead = off[t] % c
+        if n >= 32 * 256 and addr[t] % 16 == 0:
+            assert lead == (addr[t] % 1024) // 4 and (addr[t] // 4 - off[t]) % 256 == 0
+        else:
+            assert lead == 0
+        assert off[t] - lead >= end_prev and (off[t] - lead) % c == 0     # whole blocks, in order, no overlap
+        end_prev = -(-(off[t] + n) // c) * c
+    assert len(blocks) * c == end_prev                                     # and no gaps
+    pos = [0] * len(numel)
+    for b, (t, first, ln) in enumerate(blocks):
+        assert first == pos[t] and 1 <= ln <= c
+        assert b * c <= off[t] + first and off[t] + first + ln <= (b + 1) * c   # inside block b of the arena
+        pos[t] += ln
+    assert pos == list(numel)
+
+
+def test_arena_without_lead_in_is_the_chunk_plan():
+    numel = [5, 300, 8192, 70000]
+    cfg = B.make_config(numel, 2, 2, 1, 0.1, 0.9, 1e-4)
+    off, blocks, _ = B.ssd_plan_arena(cfg, [4096 * (i + 1) for i in range(4)])
+    assert blocks == B.ssd_plan_chunks(numel, 0)[0]
+    assert off == [0, 256, 768, 768 + 8192]
