@@ -36,6 +36,8 @@ PROFILE_OF = {
     ("resnet152_k4", "f32"): "profiles/ssd_fused_kernel_resnet152_K16_k4.txt",
 }
 
+CACHE_POLICY = {"auto": 0, "streaming": 1, "resident": 2}   # ssd_cache_policy
+
 # the benchmark configurations besides the headline one, and how many timed
 # steps each gets (whole k-cycles)
 OTHER_CONFIGS = (("resnet20", 200), ("resnet56", 200), ("resnet50", 40), ("resnet152_k2", 20),
@@ -79,12 +81,13 @@ def read_profile(path):
             "algorithmic": int(t.group(2).replace(",", ""))}
 
 
-def dominant_kernel_name(B, K, gd):
+def dominant_kernel_name(B, K, gd, streaming=True):
     """Name of the plain steps-delay kernel as rocprofv3 prints it: template
     arguments K, gradient element type, stage, pre_weight action, from_global,
-    exact_w_minus, workers per group, prefetch."""
+    exact_w_minus, workers per group, prefetch, non-temporal accesses."""
     G, PF = B.ssd_fused_variant(K)
-    return "ssd_fused_kernel<%d, %d, 2, 0, false, false, %d, %s>" % (K, gd, G, "true" if PF else "false")
+    return "ssd_fused_kernel<%d, %d, 2, 0, false, false, %d, %s, %s>" % (
+        K, gd, G, "true" if PF else "false", "true" if streaming else "false")
 
 
 def variant_name(kind, pa, fg):
@@ -134,8 +137,10 @@ def run_workload(torch, B, workloads, name, args, steps, warmup, P, overrides=Tr
     stream = torch.cuda.current_stream()
     chunk = args.chunk_elems if overrides else 0
     waves = args.waves_per_cu if overrides else 0
+    policy = CACHE_POLICY[args.cache_policy] if overrides else 0
     cfg = B.make_config(numel, K, k, W, wl.lr, wl.momentum, wl.wd, device=0,
-                        stream=stream.cuda_stream, chunk_elems=chunk, waves_per_cu=waves, grad_dtype=gd)
+                        stream=stream.cuda_stream, chunk_elems=chunk, waves_per_cu=waves, grad_dtype=gd,
+                        cache_policy=policy)
     ctx = B.Context(cfg, weights)
     view = ctx.ssd_get_state()
     unfused = overrides and args.unfused
@@ -256,7 +261,7 @@ def config_line(B, r):
             "ms_per_step_uninstrumented_repeat": None if r["bare_ms"] is None else round(r["bare_ms"], 5),
             "elements_per_s": r["N"] / r["sec_per_step"],
             "elements_per_s_uninstrumented_repeat": None if r["bare_ms"] is None else r["N"] / (r["bare_ms"] * 1e-3),
-            "dominant_kernel": dominant_kernel_name(B, r["K"], r["gd"]),
+            "dominant_kernel": dominant_kernel_name(B, r["K"], r["gd"], bool(r["view"].streaming)),
             "dominant_kernel_avg_ms": dom["avg_ms"], "dominant_kernel_GBps": dom["GBps"],
             "bytes_per_elem_moved": dom["bytes_per_elem_moved"],
             "frac": "launch-bound" if launch_bound else round(dom["GBps"] / HBM_PEAK_GBS, 4)}
@@ -270,6 +275,8 @@ def main():
     ap.add_argument("--workload", default="vgg16")
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--waves-per-cu", type=int, default=0)
+    ap.add_argument("--cache-policy", choices=["auto", "streaming", "resident"], default="auto",
+                    help="ssd_config.cache_policy of the fused launch (auto: the library's choice)")
     ap.add_argument("--workers", type=int, default=0, help="override K (not the benchmark configuration)")
     ap.add_argument("--delay", type=int, default=-1, help="override k (not the benchmark configuration)")
     ap.add_argument("--unfused", action="store_true",
@@ -311,7 +318,7 @@ def main():
     props = torch.cuda.get_device_properties(dev)
     P = args.pool
     overridden = bool(args.workers > 0 or args.delay >= 0 or args.chunk_elems or args.waves_per_cu or
-                      args.unfused or args.grad_skew_elems or args.grad_spacing_mib or
+                      args.cache_policy != "auto" or args.unfused or args.grad_skew_elems or args.grad_spacing_mib or
                       args.tensor_align_elems != 64)
 
     r = run_workload(torch, B, workloads, args.workload, args, args.steps, args.warmup, P)
@@ -327,9 +334,10 @@ def main():
     prof = PROFILE_OF.get((args.workload, args.grad_dtype))
     if prof and not overridden and r["dom_name"] == "delay_keep":
         pr = read_profile(prof)
-        if pr["kernel"] == dominant_kernel_name(B, K, gd) and pr["algorithmic"] == dom["bytes_per_elem_moved"] * N:
+        if pr["kernel"] == dominant_kernel_name(B, K, gd, bool(r["view"].streaming)) and pr["algorithmic"] == dom["bytes_per_elem_moved"] * N:
             traffic, traffic_source = pr["traffic"], prof
-    roofline = {"bound": "hbm", "kernel": dominant_kernel_name(B, K, gd) + " (%s)" % r["dom_name"],
+    roofline = {"bound": "hbm",
+                "kernel": dominant_kernel_name(B, K, gd, bool(r["view"].streaming)) + " (%s)" % r["dom_name"],
                 "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4),
                 "algorithmic_bytes_per_launch": dom["bytes_per_elem_moved"] * N,
@@ -390,7 +398,8 @@ def main():
     # for ever in a context with k = 0, here on the same weights and gradients
     ctx.close()
     cfg0 = B.make_config(r["numel"], K, 0, 0, wl.lr, wl.momentum, wl.wd, device=0, stream=stream.cuda_stream,
-                         chunk_elems=args.chunk_elems, waves_per_cu=args.waves_per_cu, grad_dtype=gd)
+                         chunk_elems=args.chunk_elems, waves_per_cu=args.waves_per_cu, grad_dtype=gd,
+                         cache_policy=CACHE_POLICY[args.cache_policy])
     ctx0 = B.Context(cfg0, r["weights"])
     for i in range(3):
         ctx0.ssd_step(tables[i % P])
@@ -430,6 +439,7 @@ def main():
                    "gradient_buffers": args.grad_dtype,
                    "chunk_elems": view.chunk_elems, "num_chunks": view.num_chunks,
                    "waves_per_cu": args.waves_per_cu or "library default",
+                   "cache_policy": "streaming" if view.streaming else "resident",
                    "gradient_sets_cycled": P, "seed": wl.seed, "lr": wl.lr, "momentum": wl.momentum,
                    "wd": wl.wd, "device": props.name, "compute_units": props.multi_processor_count,
                    "arch": getattr(props, "gcnArchName", None)},

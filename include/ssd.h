@@ -82,6 +82,15 @@ enum ssd_grad_dtype {
     SSD_GRAD_F16 = 2   /* IEEE binary16                                        */
 };
 
+/* How the fused kernel marks its global loads and stores. */
+enum ssd_cache_policy {
+    SSD_CACHE_AUTO = 0,      /* the library's choice (see ssd_config)            */
+    SSD_CACHE_STREAMING = 1, /* non-temporal: every byte of an iteration is
+                                touched once and nothing fits a cache           */
+    SSD_CACHE_RESIDENT = 2   /* ordinary accesses: the arrays of a small model
+                                stay in the last-level cache between iterations */
+};
+
 typedef struct ssd_ctx ssd_ctx; /* opaque */
 
 /* Configuration.  Symbols follow Table 1 of the paper. */
@@ -114,6 +123,13 @@ typedef struct {
                               Sec. 3.2.1, ((1 - lr*wd)*pre_weight - w')       */
     int32_t grad_dtype;    /* an ssd_grad_dtype: element type of every gradient
                               buffer passed to this context                   */
+    int32_t cache_policy;  /* an ssd_cache_policy for the fused launch; 0 = the
+                              library's choice: resident (ordinary accesses,
+                              no cap on resident waves) if the arrays one
+                              iteration touches -- K gradients, K local
+                              weights, weight, momentum, pre_weight -- fit
+                              the 256 MiB last-level cache of MI355X, else
+                              streaming.  Results never depend on it.         */
 } ssd_config;
 
 /* Device-side state, for inspection.  All arrays are "arena" arrays of
@@ -138,6 +154,8 @@ typedef struct {
     int32_t w_loc_where;    /* where w_loc_i (what the next forward/backward
                                uses) is: an ssd_w_loc_where value             */
     int32_t chunk_elems;
+    int32_t streaming;      /* 1: the fused launch uses non-temporal accesses
+                               (SSD_CACHE_STREAMING), 0: ordinary ones         */
     int64_t num_chunks;
     int64_t arena_elems;
     const int64_t *tensor_offset; /* host [T], owned by the context           */

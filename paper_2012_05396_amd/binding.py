@@ -17,6 +17,7 @@ SSD_STEP_WARMUP, SSD_STEP_WARMUP_LAST, SSD_STEP_DELAY, SSD_STEP_DELAY_PULL = 0, 
 SSD_PRE_KEEP, SSD_PRE_INIT, SSD_PRE_REFRESH = 0, 1, 2
 SSD_W_LOC_IS_GLOBAL, SSD_W_LOC_IN_W_LOCAL, SSD_W_LOC_SEPARATE = 0, 1, 2
 SSD_GRAD_F32, SSD_GRAD_BF16, SSD_GRAD_F16 = 0, 1, 2
+SSD_CACHE_AUTO, SSD_CACHE_STREAMING, SSD_CACHE_RESIDENT = 0, 1, 2
 GRAD_TORCH_DTYPE = {SSD_GRAD_F32: torch.float32, SSD_GRAD_BF16: torch.bfloat16,
                     SSD_GRAD_F16: torch.float16}
 
@@ -32,14 +33,15 @@ class ssd_config(C.Structure):
                 ("numel", C.POINTER(C.c_int64)),
                 ("device", C.c_int32), ("stream", C.c_void_p),
                 ("chunk_elems", C.c_int32), ("waves_per_cu", C.c_int32),
-                ("grad_sync_exact", C.c_int32), ("grad_dtype", C.c_int32)]
+                ("grad_sync_exact", C.c_int32), ("grad_dtype", C.c_int32),
+                ("cache_policy", C.c_int32)]
 
 
 class ssd_state_view(C.Structure):
     _fields_ = [("iterations", C.c_int64), ("local_updates", C.c_int64),
                 ("in_delay_stage", C.c_int32), ("has_local", C.c_int32),
                 ("w_local_is_global", C.c_int32), ("w_loc_where", C.c_int32),
-                ("chunk_elems", C.c_int32),
+                ("chunk_elems", C.c_int32), ("streaming", C.c_int32),
                 ("num_chunks", C.c_int64), ("arena_elems", C.c_int64),
                 ("tensor_offset", C.POINTER(C.c_int64)),
                 ("mom", C.c_void_p), ("pre", C.c_void_p),
@@ -174,7 +176,7 @@ def ssd_fused_variant(K):
 
 def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=None, beta=None, wd_loc=None,
                 rescale_grad=None, device=0, stream=None, chunk_elems=0, waves_per_cu=0,
-                grad_sync_exact=0, grad_dtype=SSD_GRAD_F32):
+                grad_sync_exact=0, grad_dtype=SSD_GRAD_F32, cache_policy=0):
     """ssd_config: the library's defaults (ssd_config_defaults: loc_lr = 4*lr,
     alpha = 2, beta = 0.5, averaged gradient, wd_loc = wd), then whatever the
     caller overrides.  Returns the struct; it keeps the numel array alive."""
@@ -188,7 +190,7 @@ def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=None, beta=
             setattr(cfg, name, val)
     cfg.num_tensors, cfg.numel, cfg.device, cfg.stream = T, arr, device, stream
     cfg.chunk_elems, cfg.waves_per_cu = chunk_elems, waves_per_cu
-    cfg.grad_sync_exact, cfg.grad_dtype = grad_sync_exact, grad_dtype
+    cfg.grad_sync_exact, cfg.grad_dtype, cfg.cache_policy = grad_sync_exact, grad_dtype, cache_policy
     cfg._keep = arr
     return cfg
 

@@ -202,31 +202,40 @@ typedef __attribute__((address_space(1))) const float cgfloat;
 static __device__ __forceinline__ gfloat *ssd_global(float *p) { return (gfloat *)p; }
 static __device__ __forceinline__ cgfloat *ssd_global(const float *p) { return (cgfloat *)p; }
 
-// VW-wide (1 or 4 floats) global loads and stores.  Every byte of the step is
-// touched once, so both are marked non-temporal.
-template <int VW> struct ssd_vec;
-template <> struct ssd_vec<1> {
+// VW-wide (1 or 4 floats) global loads and stores.  NT: every byte of a step
+// is touched once and the arrays are far larger than the caches, so both are
+// marked non-temporal.  !NT: ordinary accesses, for models whose whole state
+// stays in the last-level cache from one iteration to the next.
+template <int VW, bool NT = true> struct ssd_vec;
+template <bool NT> struct ssd_vec<1, NT> {
     static __device__ __forceinline__ void ld(cgfloat *p, float (&x)[1])
     {
-        x[0] = __builtin_nontemporal_load(p);
+        x[0] = NT ? __builtin_nontemporal_load(p) : *p;
     }
     static __device__ __forceinline__ void st(gfloat *p, const float (&x)[1])
     {
-        __builtin_nontemporal_store(x[0], p);
+        if (NT)
+            __builtin_nontemporal_store(x[0], p);
+        else
+            *p = x[0];
     }
 };
-template <> struct ssd_vec<4> {
+template <bool NT> struct ssd_vec<4, NT> {
     typedef float v4 __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(1))) v4 gv4;
     typedef __attribute__((address_space(1))) const v4 cgv4;
     static __device__ __forceinline__ void ld(cgfloat *p, float (&x)[4])
     {
-        v4 v = __builtin_nontemporal_load((cgv4 *)p);
+        v4 v = NT ? __builtin_nontemporal_load((cgv4 *)p) : *(cgv4 *)p;
         x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
     }
     static __device__ __forceinline__ void st(gfloat *p, const float (&x)[4])
     {
         v4 v = {x[0], x[1], x[2], x[3]};
+        if (!NT) {
+            *(gv4 *)p = v;
+            return;
+        }
         // "sc1 nt" (system-coherence bit + non-temporal) is a cache policy the
         // compiler has no builtin for; measured 1-2 % faster than plain "nt"
         // on MI355X.  The compiler cannot see into the asm, so the wait
@@ -258,43 +267,46 @@ template <> struct ssd_grad<SSD_GRAD_F16> {
     typedef uint16_t elem;
 };
 
-template <int GD, int VW> struct ssd_gvec;
-template <int VW> struct ssd_gvec<SSD_GRAD_F32, VW> {
+template <int GD, int VW, bool NT = true> struct ssd_gvec;
+template <int VW, bool NT> struct ssd_gvec<SSD_GRAD_F32, VW, NT> {
     typedef cgfloat *ptr;
-    static __device__ __forceinline__ void ld(ptr p, float (&x)[VW]) { ssd_vec<VW>::ld(p, x); }
+    static __device__ __forceinline__ void ld(ptr p, float (&x)[VW]) { ssd_vec<VW, NT>::ld(p, x); }
 };
-template <> struct ssd_gvec<SSD_GRAD_BF16, 1> {
+template <bool NT> struct ssd_gvec<SSD_GRAD_BF16, 1, NT> {
     typedef __attribute__((address_space(1))) const uint16_t *ptr;
     static __device__ __forceinline__ void ld(ptr p, float (&x)[1])
     {
-        x[0] = __uint_as_float((uint32_t)__builtin_nontemporal_load(p) << 16);
+        x[0] = __uint_as_float((uint32_t)(NT ? __builtin_nontemporal_load(p) : *p) << 16);
     }
 };
-template <> struct ssd_gvec<SSD_GRAD_BF16, 4> {
+template <bool NT> struct ssd_gvec<SSD_GRAD_BF16, 4, NT> {
     typedef __attribute__((address_space(1))) const uint16_t *ptr;
     typedef uint32_t u2 __attribute__((ext_vector_type(2)));
     static __device__ __forceinline__ void ld(ptr p, float (&x)[4])
     {
-        const u2 v = __builtin_nontemporal_load((__attribute__((address_space(1))) const u2 *)p);
+        typedef __attribute__((address_space(1))) const u2 *gp2;
+        const u2 v = NT ? __builtin_nontemporal_load((gp2)p) : *(gp2)p;
         x[0] = __uint_as_float(v.x << 16);
         x[1] = __uint_as_float(v.x & 0xffff0000u);
         x[2] = __uint_as_float(v.y << 16);
         x[3] = __uint_as_float(v.y & 0xffff0000u);
     }
 };
-template <> struct ssd_gvec<SSD_GRAD_F16, 1> {
+template <bool NT> struct ssd_gvec<SSD_GRAD_F16, 1, NT> {
     typedef __attribute__((address_space(1))) const uint16_t *ptr;
     static __device__ __forceinline__ void ld(ptr p, float (&x)[1])
     {
-        x[0] = (float)__builtin_nontemporal_load((__attribute__((address_space(1))) const _Float16 *)p);
+        typedef __attribute__((address_space(1))) const _Float16 *gph;
+        x[0] = (float)(NT ? __builtin_nontemporal_load((gph)p) : *(gph)p);
     }
 };
-template <> struct ssd_gvec<SSD_GRAD_F16, 4> {
+template <bool NT> struct ssd_gvec<SSD_GRAD_F16, 4, NT> {
     typedef __attribute__((address_space(1))) const uint16_t *ptr;
     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
     static __device__ __forceinline__ void ld(ptr p, float (&x)[4])
     {
-        const h4 v = __builtin_nontemporal_load((__attribute__((address_space(1))) const h4 *)p);
+        typedef __attribute__((address_space(1))) const h4 *gp4;
+        const h4 v = NT ? __builtin_nontemporal_load((gp4)p) : *(gp4)p;
         x[0] = (float)v.x; x[1] = (float)v.y; x[2] = (float)v.z; x[3] = (float)v.w;
     }
 };
@@ -322,13 +334,14 @@ hipError_t ssd_launch_fill_zero(float *p, int64_t n, hipStream_t s);
 // lds_bytes: LDS slice per workgroup (occupancy cap, 0 = none); lds_limit: the
 // largest slice any launch on this device may ask for (LDS per compute unit)
 typedef hipError_t (*ssd_fused_launcher)(int stage, int pre_action, int from_global, int exact_w_minus,
+                                         int streaming,
                                          unsigned lds_bytes, unsigned lds_limit,
                                          unsigned nchunks, hipStream_t s, const ssd_fused_args &a);
 // ssd_launch_fused_g<grad_dtype>_k<K>
 #define SSD_DECL_FUSED(k)                                                                                        \
-    hipError_t ssd_launch_fused_g0_k##k(int, int, int, int, unsigned, unsigned, unsigned, hipStream_t, const ssd_fused_args &); \
-    hipError_t ssd_launch_fused_g1_k##k(int, int, int, int, unsigned, unsigned, unsigned, hipStream_t, const ssd_fused_args &); \
-    hipError_t ssd_launch_fused_g2_k##k(int, int, int, int, unsigned, unsigned, unsigned, hipStream_t, const ssd_fused_args &);
+    hipError_t ssd_launch_fused_g0_k##k(int, int, int, int, int, unsigned, unsigned, unsigned, hipStream_t, const ssd_fused_args &); \
+    hipError_t ssd_launch_fused_g1_k##k(int, int, int, int, int, unsigned, unsigned, unsigned, hipStream_t, const ssd_fused_args &); \
+    hipError_t ssd_launch_fused_g2_k##k(int, int, int, int, int, unsigned, unsigned, unsigned, hipStream_t, const ssd_fused_args &);
 SSD_DECL_FUSED(1) SSD_DECL_FUSED(2) SSD_DECL_FUSED(3) SSD_DECL_FUSED(4)
 SSD_DECL_FUSED(5) SSD_DECL_FUSED(6) SSD_DECL_FUSED(7) SSD_DECL_FUSED(8)
 SSD_DECL_FUSED(9) SSD_DECL_FUSED(10) SSD_DECL_FUSED(11) SSD_DECL_FUSED(12)

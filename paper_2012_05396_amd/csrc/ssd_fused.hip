@@ -33,6 +33,10 @@
 // whenever every caller pointer of the tensor is 16-byte aligned, else element
 // by element.
 //
+// NT selects the marking of every global access: non-temporal for models
+// that stream through HBM, ordinary for models whose arrays stay in the
+// last-level cache from one iteration to the next (the host decides by size).
+//
 // Compiled once per K (-DSSD_K=1..16) so that the worker loops unroll, and per
 // element type of the gradient buffers (-DSSD_GD=0..2).
 #include "ssd_device.h"
@@ -55,34 +59,34 @@ template <int G, int VW> struct ssd_head_regs {
     ssd_group_regs<G, VW> grp; // .wl of group 0
 };
 
-template <int K, int STAGE, bool FG, int G, int VW>
+template <int K, int STAGE, bool FG, int G, bool NT, int VW>
 __device__ __forceinline__ void ssd_load_wl(int j, gfloat *wlp, int64_t A, unsigned e,
                                             ssd_group_regs<G, VW> &r)
 {
     if (STAGE == SSD_STAGE_DELAY && !FG) {
 #pragma unroll
         for (int i = 0; i < G; ++i)
-            if (j * G + i < K) ssd_vec<VW>::ld(wlp + (int64_t)(j * G + i) * A + e, r.wl[i]);
+            if (j * G + i < K) ssd_vec<VW, NT>::ld(wlp + (int64_t)(j * G + i) * A + e, r.wl[i]);
     }
 }
 
-template <int K, int GD, int G, int VW>
+template <int K, int GD, int G, bool NT, int VW>
 __device__ __forceinline__ void ssd_load_g(int j, const typename ssd_gvec<GD, 4>::ptr (&gp)[K], unsigned e,
                                            ssd_group_regs<G, VW> &r)
 {
 #pragma unroll
     for (int i = 0; i < G; ++i)
-        if (j * G + i < K) ssd_gvec<GD, VW>::ld(gp[j * G + i] + e, r.g[i]);
+        if (j * G + i < K) ssd_gvec<GD, VW, NT>::ld(gp[j * G + i] + e, r.g[i]);
 }
 
-template <int K, int STAGE, int PRE, bool FG, int G, int VW>
+template <int K, int STAGE, int PRE, bool FG, int G, bool NT, int VW>
 __device__ __forceinline__ void ssd_load_head(gfloat *momp, gfloat *prep, gfloat *wlp, int64_t A, unsigned e,
                                               ssd_head_regs<G, VW> &s)
 {
-    ssd_vec<VW>::ld(momp + e, s.mo);
+    ssd_vec<VW, NT>::ld(momp + e, s.mo);
     if (STAGE == SSD_STAGE_DELAY) {
-        if (PRE != SSD_PRE_INIT) ssd_vec<VW>::ld(prep + e, s.p);
-        ssd_load_wl<K, STAGE, FG, G, VW>(0, wlp, A, e, s.grp);
+        if (PRE != SSD_PRE_INIT) ssd_vec<VW, NT>::ld(prep + e, s.p);
+        ssd_load_wl<K, STAGE, FG, G, NT, VW>(0, wlp, A, e, s.grp);
     }
 }
 
@@ -95,24 +99,24 @@ __device__ __forceinline__ void ssd_load_head(gfloat *momp, gfloat *prep, gfloat
 // after such a store would also wait for the store's acknowledgement; and
 // left to itself the scheduler then also sinks late gradient loads below
 // arithmetic on early ones (16-bit gradient kernels: 5.85 instead of 6.39 TB/s).
-template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF, int VW>
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF, bool NT, int VW>
 __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ssd_gvec<GD, 4>::ptr (&gp)[K],
                                            gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t A,
                                            unsigned e, const ssd_head_regs<G, VW> &s)
 {
-    typedef ssd_vec<VW> V;
+    typedef ssd_vec<VW, NT> V;
     constexpr int NG = (K + G - 1) / G;
     ssd_group_regs<G, VW> cur = s.grp;
     float w[VW], S[VW], wn[VW], mn[VW];
-    ssd_load_g<K, GD, G, VW>(0, gp, e, cur);
+    ssd_load_g<K, GD, G, NT, VW>(0, gp, e, cur);
     V::ld(wp + e, w);
 
 #pragma unroll
     for (int j = 0; j < NG; ++j) {
         ssd_group_regs<G, VW> nxt = {};
         if (PF && j + 1 < NG) {
-            ssd_load_wl<K, STAGE, FG, G, VW>(j + 1, wlp, A, e, nxt);
-            ssd_load_g<K, GD, G, VW>(j + 1, gp, e, nxt);
+            ssd_load_wl<K, STAGE, FG, G, NT, VW>(j + 1, wlp, A, e, nxt);
+            ssd_load_g<K, GD, G, NT, VW>(j + 1, gp, e, nxt);
         }
         // Eq. (server): the sum of the K gradients, in worker order
 #pragma unroll
@@ -150,8 +154,8 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
             }
         }
         if (!PF && j + 1 < NG) {
-            ssd_load_wl<K, STAGE, FG, G, VW>(j + 1, wlp, A, e, nxt);
-            ssd_load_g<K, GD, G, VW>(j + 1, gp, e, nxt);
+            ssd_load_wl<K, STAGE, FG, G, NT, VW>(j + 1, wlp, A, e, nxt);
+            ssd_load_g<K, GD, G, NT, VW>(j + 1, gp, e, nxt);
         }
         if (j + 1 < NG) cur = nxt;
     }
@@ -169,14 +173,14 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
 // the 128-bit path; a lane at a ragged end of the block, or any lane when a
 // caller pointer is not 16-byte aligned, goes element by element -- in both
 // cases with the head state preloaded in `s`.
-template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF>
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF, bool NT>
 __device__ __forceinline__ void ssd_tile(const ssd_hyper &h, const typename ssd_gvec<GD, 4>::ptr (&gp)[K],
                                          gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t A,
                                          unsigned e0, unsigned lo, unsigned len, bool vec,
                                          const ssd_head_regs<G, 4> &s)
 {
     if (vec && e0 >= lo && e0 + 3 < len) {
-        ssd_finish<K, GD, STAGE, PRE, FG, XW, G, PF, 4>(h, gp, wp, momp, prep, wlp, A, e0, s);
+        ssd_finish<K, GD, STAGE, PRE, FG, XW, G, PF, NT, 4>(h, gp, wp, momp, prep, wlp, A, e0, s);
     } else if (e0 + 3 >= lo && e0 < len) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -186,7 +190,7 @@ __device__ __forceinline__ void ssd_tile(const ssd_hyper &h, const typename ssd_
                 s1.p[0] = s.p[v];
 #pragma unroll
                 for (int i = 0; i < G; ++i) s1.grp.wl[i][0] = s.grp.wl[i][v];
-                ssd_finish<K, GD, STAGE, PRE, FG, XW, G, false, 1>(h, gp, wp, momp, prep, wlp, A, e0 + v, s1);
+                ssd_finish<K, GD, STAGE, PRE, FG, XW, G, false, NT, 1>(h, gp, wp, momp, prep, wlp, A, e0 + v, s1);
             }
         }
     }
@@ -195,7 +199,7 @@ __device__ __forceinline__ void ssd_tile(const ssd_hyper &h, const typename ssd_
 // The arguments a wave needs first come as separate leading kernel arguments
 // so that they can be preloaded into scalar registers at wave launch
 // (-amdgpu-kernarg-preload-count); the rest arrives with ordinary scalar loads.
-template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF>
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF, bool NT>
 __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *block_tensor, float *mom,
                                                               float *pre, float *wl, int64_t A,
                                                               unsigned C, unsigned blocks_per_xcd,
@@ -212,7 +216,7 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
     gfloat *momp = ssd_global(mom) + ao, *prep = ssd_global(pre) + ao;
     gfloat *wlp = ssd_global(wl) + ao;
     ssd_head_regs<G, 4> s;
-    ssd_load_head<K, STAGE, PRE, FG, G, 4>(momp, prep, wlp, A, lane * 4, s);
+    ssd_load_head<K, STAGE, PRE, FG, G, NT, 4>(momp, prep, wlp, A, lane * 4, s);
 
     // block -> tensor -> one record {w, elem0, numel, g_0 .. g_{K-1}}
     // and the tensor's hyper-parameters
@@ -235,10 +239,10 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
 
     unsigned base = 0;
     for (;;) {
-        ssd_tile<K, GD, STAGE, PRE, FG, XW, G, PF>(h, gp, wp, momp, prep, wlp, A, base + lane * 4, lo, len, vec, s);
+        ssd_tile<K, GD, STAGE, PRE, FG, XW, G, PF, NT>(h, gp, wp, momp, prep, wlp, A, base + lane * 4, lo, len, vec, s);
         base += SSD_BLOCK * 4;
         if (base >= len) break; // uniform
-        ssd_load_head<K, STAGE, PRE, FG, G, 4>(momp, prep, wlp, A, base + lane * 4, s);
+        ssd_load_head<K, STAGE, PRE, FG, G, NT, 4>(momp, prep, wlp, A, base + lane * 4, s);
     }
 }
 
@@ -262,7 +266,7 @@ static hipError_t ssd_allow_lds(Kernel kernel, unsigned lds, unsigned long long 
     return e;
 }
 
-hipError_t SSD_CAT(SSD_CAT(SSD_CAT(ssd_launch_fused_g, SSD_GD), _k), SSD_K)(int stage, int pre_action, int from_global, int exact_w_minus,
+hipError_t SSD_CAT(SSD_CAT(SSD_CAT(ssd_launch_fused_g, SSD_GD), _k), SSD_K)(int stage, int pre_action, int from_global, int exact_w_minus, int streaming,
                                                unsigned lds_bytes, unsigned lds_limit, unsigned nchunks, hipStream_t s,
                                                const ssd_fused_args &a)
 {
@@ -272,7 +276,12 @@ hipError_t SSD_CAT(SSD_CAT(SSD_CAT(ssd_launch_fused_g, SSD_GD), _k), SSD_K)(int 
     // lds_bytes: the occupancy cap, a slice of LDS that is never accessed
 #define SSD_GO(ST, PR, FG, XW)                                                                     \
     do {                                                                                           \
-        auto kernel = ssd_fused_kernel<SSD_K, SSD_GD, ST, PR, FG, XW, G, PF>;                      \
+        if (streaming) SSD_GO_NT(ST, PR, FG, XW, true);                                            \
+        SSD_GO_NT(ST, PR, FG, XW, false);                                                          \
+    } while (0)
+#define SSD_GO_NT(ST, PR, FG, XW, NT)                                                              \
+    do {                                                                                           \
+        auto kernel = ssd_fused_kernel<SSD_K, SSD_GD, ST, PR, FG, XW, G, PF, NT>;                  \
         if (lds_bytes > 65536) {                                                                   \
             static unsigned long long done = 0;                                                    \
             const hipError_t e = ssd_allow_lds(kernel, lds_limit, done);                           \

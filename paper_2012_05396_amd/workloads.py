@@ -146,6 +146,13 @@ def workload(name):
         return _wl(name, alexnet(), 4, 5, 20, seed=106)
     if name == "vgg11":
         return _wl(name, vgg11(), 4, 5, 20, seed=107)
+    # any CIFAR ResNet-(6n+2), e.g. cifar_resnet110: sizes between the benchmark
+    # configurations, for sweeps (K = 8, k = 4 like the ResNet-56 one)
+    if name.startswith("cifar_resnet"):
+        depth = int(name[len("cifar_resnet"):])
+        if depth < 8 or (depth - 2) % 6:
+            raise KeyError(name)
+        return _wl(name, cifar_resnet((depth - 2) // 6), 8, 4, 20, grad_fan_in_scale=True, seed=108)
     raise KeyError(name)
 
 

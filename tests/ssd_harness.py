@@ -139,19 +139,60 @@ def compare_state(ctx, model, o, exact=True, tol=1e-5, where=""):
     return worst[0]
 
 
+def same_bits(a, b):
+    return torch.equal(a.contiguous().view(torch.int32), b.contiguous().view(torch.int32))
+
+
+def assert_twin_equal(ctx, weights, twin, twin_weights, where=""):
+    """Two contexts that took the same steps hold the same bits (compared on the
+    GPU, tensor by tensor: their arena layouts may differ)."""
+    v, u = ctx.ssd_get_state(), twin.ssd_get_state()
+    for f in ("iterations", "local_updates", "in_delay_stage", "has_local", "w_local_is_global", "w_loc_where"):
+        assert getattr(v, f) == getattr(u, f), (where, f)
+    pairs = list(zip(weights, twin_weights)) + list(zip(ctx.state_tensors("mom"), twin.state_tensors("mom")))
+    if ctx.cfg.delay_k > 0 and v.has_local:
+        if v.local_updates > 0:
+            pairs += list(zip(ctx.state_tensors("pre"), twin.state_tensors("pre")))
+        for i in range(ctx.K):
+            # the w' arrays: w'_i, or -- while w' is the global weight -- the broadcast local weights
+            if not v.w_local_is_global or v.w_loc_where == 1:
+                pairs += list(zip(ctx.state_tensors("w_local", i), twin.state_tensors("w_local", i)))
+            if v.w_loc_where == 2:
+                pairs += list(zip(ctx.state_tensors("w_loc", i), twin.state_tensors("w_loc", i)))
+    for n, (a, b) in enumerate(pairs):
+        assert same_bits(a, b), "%s: the two cache policies differ in array %d" % (where, n)
+
+
 def run_schedule(numel, K, k, W, steps, hp=None, mode="f32", chunk_elems=256, seed=0,
                  w_shift=0, g_shift=0, g_scale=1e-2, check_every=1, P=3, lr_changes=None,
                  grad_dtype=0):
     """Drive ssd_step and the oracle side by side; compare after each step.
-    grad_dtype: an ssd_grad_dtype value."""
+    grad_dtype: an ssd_grad_dtype value.  Unless hp names a cache_policy, the
+    compared context runs the streaming kernels (the ones large models get) and
+    a twin on a copy of the weights runs the resident ones (what the library
+    would choose for inputs this small); the twin must hold the same bits."""
     from paper_2012_05396_amd import binding as B
     hp = dict(lr=0.1, momentum=0.9, wd=1e-4) if hp is None else dict(hp)
     model = Model(numel, K, P=P, seed=seed, w_shift=w_shift, g_shift=g_shift, g_scale=g_scale,
                   grad_dtype=B.GRAD_TORCH_DTYPE[grad_dtype])
+    both = "cache_policy" not in hp
+    if both:
+        hp["cache_policy"] = B.SSD_CACHE_STREAMING
     cfg = B.make_config(numel, K, k, W, device=0,
                         stream=torch.cuda.current_stream().cuda_stream,
                         chunk_elems=chunk_elems, grad_dtype=grad_dtype, **hp)
     ctx = B.Context(cfg, model.weights)
+    twin = None
+    if both:
+        twin_flat = model.wflat.clone()
+        base = model.wflat.data_ptr()
+        twin_weights = [twin_flat[(w.data_ptr() - base) // 4:(w.data_ptr() - base) // 4 + w.numel()]
+                        for w in model.weights]
+        tcfg = B.make_config(numel, K, k, W, device=0, stream=torch.cuda.current_stream().cuda_stream,
+                             chunk_elems=chunk_elems, grad_dtype=grad_dtype,
+                             **dict(hp, cache_policy=B.SSD_CACHE_RESIDENT))
+        twin = B.Context(tcfg, twin_weights)
+        assert ctx.ssd_get_state().streaming == 1 and twin.ssd_get_state().streaming == 0
     ohp = dict(lr=hp["lr"], m=hp["momentum"], wd=hp["wd"])
     for a in ("lr_loc", "alpha", "beta", "wd_loc"):
         if a in hp:
@@ -167,13 +208,21 @@ def run_schedule(numel, K, k, W, steps, hp=None, mode="f32", chunk_elems=256, se
         if lr_changes and it in lr_changes:
             lr, lr_loc = lr_changes[it]
             ctx.ssd_set_lr(lr, lr_loc)
+            if twin:
+                twin.ssd_set_lr(lr, lr_loc)
             o.set_lr(lr, lr_loc)
         p = it % P
         kind, _ = B.ssd_step_kind_of(it, W, k, o.d)
         ctx.ssd_step(tables[p])
+        if twin:
+            twin.ssd_step(tables[p])
         okind = o.step(model.g_host[p])
         assert kind == okind
         if (it + 1) % check_every == 0 or it == steps - 1:
             compare_state(ctx, model, o, exact=exact, where="it=%d kind=%d" % (it, kind))
+            if twin:
+                assert_twin_equal(ctx, model.weights, twin, twin_weights, where="it=%d kind=%d" % (it, kind))
     ctx.close()
+    if twin:
+        twin.close()
     return model, o

@@ -69,6 +69,9 @@ def run_full(name, piecewise_check=False, wl=None, grad_dtype=0, tol_elem=1e-5):
     ctx = B.Context(mk(), weights)
     v = ctx.ssd_get_state()
     assert v.chunk_elems == 256
+    # the library's own choice of cache policy: ordinary accesses while one iteration's arrays fit 256 MiB
+    touched = v.num_chunks * v.chunk_elems * (K * (4 if grad_dtype == 0 else 2) + 4 * (K + 3))
+    assert v.streaming == (1 if touched > 256 << 20 else 0) and (v.streaming == 1 or sum(numel) < 2_000_000)
 
     # sample: indices into the caller's flat buffers and into the arena
     flat_idx, arena_idx, seg_start, seg_len = [], [], [], []

@@ -164,3 +164,30 @@ def test_refusals_without_a_delay_stage():
     o.step(m.g_host[0])
     compare_state(ctx, m, o, where="k = 0 after refusals")
     ctx.close()
+
+
+def test_cache_policy_choice_and_override():
+    """Auto: ordinary accesses (and no occupancy cap) while everything one
+    iteration touches fits the 256 MiB last-level cache, else non-temporal ones;
+    either can be forced.  Bits never depend on it (every schedule test runs
+    both policies side by side); here: what the state view reports."""
+    print("case: cache policy", flush=True)
+    numel = [300000, 70000]          # 370 K elements: 35 arrays at K = 16 are 52 MB
+    w = [torch.zeros(n, device="cuda") for n in numel]
+    stream = torch.cuda.current_stream().cuda_stream
+    for policy, expect in ((B.SSD_CACHE_AUTO, 0), (B.SSD_CACHE_STREAMING, 1), (B.SSD_CACHE_RESIDENT, 0)):
+        ctx = B.Context(B.make_config(numel, 16, 2, 1, 0.1, 0.9, 1e-4, stream=stream, cache_policy=policy), w)
+        assert ctx.ssd_get_state().streaming == expect
+        ctx.close()
+    # 8 Mi elements: K = 1 touches 5 arrays = 160 MiB -> resident; K = 4 touches 11 = 352 MiB -> streaming
+    big = [torch.zeros(8 << 20, device="cuda")]
+    for K, expect in ((1, 0), (4, 1)):
+        ctx = B.Context(B.make_config([8 << 20], K, 2, 1, 0.1, 0.9, 1e-4, stream=stream), big)
+        assert ctx.ssd_get_state().streaming == expect
+        ctx.close()
+    # 16-bit gradients count half: K = 3 with bfloat16 touches 3*2 + 6*4 = 30 B per element = 240 MiB -> resident,
+    # with binary32 gradients 36 B = 288 MiB -> streaming
+    for gd, expect in ((B.SSD_GRAD_BF16, 0), (B.SSD_GRAD_F32, 1)):
+        ctx = B.Context(B.make_config([8 << 20], 3, 2, 1, 0.1, 0.9, 1e-4, stream=stream, grad_dtype=gd), big)
+        assert ctx.ssd_get_state().streaming == expect
+        ctx.close()

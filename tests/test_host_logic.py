@@ -126,7 +126,7 @@ def _cfg(**kw):
 @pytest.mark.parametrize("kw", [dict(K=0), dict(K=17), dict(k=-1), dict(W=-1), dict(numel=[3, 0]),
                                 dict(lr=0.0), dict(chunk_elems=100), dict(device=-1),
                                 dict(waves_per_cu=-2), dict(grad_dtype=3), dict(grad_dtype=-1),
-                                dict(grad_sync_exact=2)])
+                                dict(grad_sync_exact=2), dict(cache_policy=3), dict(cache_policy=-1)])
 def test_workspace_bytes_rejects_bad_config(kw):
     with pytest.raises(B.SsdError) as e:
         B.ssd_workspace_bytes(_cfg(**kw))
