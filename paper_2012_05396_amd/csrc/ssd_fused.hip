@@ -39,6 +39,8 @@
 //
 // Compiled once per K (-DSSD_K=1..16) so that the worker loops unroll, and per
 // element type of the gradient buffers (-DSSD_GD=0..2).
+#include <atomic>
+
 #include "ssd_device.h"
 
 #ifndef SSD_K
@@ -251,18 +253,20 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
 
 // A slice of LDS above 64 KiB needs the kernel's dynamic-LDS limit raised;
 // that is a property of the kernel on a device, set once per kernel variant
-// and device (bit d of `done`), not per launch.
+// and device (bit d of `done`), not per launch.  Contexts on different host
+// threads share the word: two of them may both set the attribute the first
+// time (harmless, same value), never read a torn word.
 template <typename Kernel>
-static hipError_t ssd_allow_lds(Kernel kernel, unsigned lds, unsigned long long &done)
+static hipError_t ssd_allow_lds(Kernel kernel, unsigned lds, std::atomic<unsigned long long> &done)
 {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    const unsigned long long bit = 1ull << (dev & 63);
-    if (done & bit) return hipSuccess;
+    const unsigned long long bit = dev < 64 ? 1ull << dev : 0; // beyond 64 devices: set it every time
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds);
-    if (e == hipSuccess) done |= bit;
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
     return e;
 }
 
@@ -283,7 +287,7 @@ hipError_t SSD_CAT(SSD_CAT(SSD_CAT(ssd_launch_fused_g, SSD_GD), _k), SSD_K)(int 
     do {                                                                                           \
         auto kernel = ssd_fused_kernel<SSD_K, SSD_GD, ST, PR, FG, XW, G, PF, NT>;                  \
         if (lds_bytes > 65536) {                                                                   \
-            static unsigned long long done = 0;                                                    \
+            static std::atomic<unsigned long long> done{0};                                        \
             const hipError_t e = ssd_allow_lds(kernel, lds_limit, done);                           \
             if (e != hipSuccess) return e;                                                         \
         }                                                                                          \
