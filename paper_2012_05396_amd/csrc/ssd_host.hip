@@ -723,14 +723,14 @@ static int check_grads(ssd_ctx *c, const void *const *const *grads)
 // Beyond K = 8 a wave takes the workers in groups of 4, two groups requested
 // at a time, so its loads in flight no longer grow with K; measured at K = 9,
 // 10, 12, 14, 16: 4 waves for the plain kernel (5 at K = 9), 6 for the
-// from-global and the warm-up kernel (which have no local weights to read, so
-// half the loads in flight); with 16-bit gradients (half-size gradient loads;
-// K = 16) 5, 6 and 8.
+// from-global (5 at K = 16: +2 % in three sessions) and the warm-up kernel
+// (which have no local weights to read, so half the loads in flight); with
+// 16-bit gradients (half-size gradient loads; K = 16) 5, 6 and 8.
 static int default_waves_per_cu(int K, int stage, int from_global, bool grad16)
 {
     if (K > 8) {
         if (stage == SSD_STAGE_WARMUP) return grad16 ? 8 : 6;
-        if (from_global) return 6;
+        if (from_global) return (K == 16 && !grad16) ? 5 : 6;
         return (grad16 || K == 9) ? 5 : 4;
     }
     int loads2, budget, floor_n; // loads per lane in halves of a 128-bit load
