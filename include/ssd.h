@@ -17,7 +17,8 @@
  *     that the library reads during the call only (it keeps no reference).
  *   - Calls enqueue work on the stream given at ssd_init and return without
  *     waiting for it.  Ordering against the caller's other GPU work is stream
- *     order.  A context must be used from one host thread at a time.
+ *     order.  A context must be used from one host thread at a time;
+ *     different contexts may be used from different threads at once.
  *   - Return value: SSD_OK (0) or a negative SSD_E* code.  Arguments are
  *     checked before anything is enqueued, so a failing call leaves the state
  *     untouched.  ssd_last_error gives a message for the last failure.

@@ -191,3 +191,42 @@ def test_cache_policy_choice_and_override():
         ctx = B.Context(B.make_config([8 << 20], 3, 2, 1, 0.1, 0.9, 1e-4, stream=stream, grad_dtype=gd), big)
         assert ctx.ssd_get_state().streaming == expect
         ctx.close()
+
+
+def test_two_contexts_on_two_host_threads():
+    """A context belongs to one host thread at a time; different contexts may
+    be driven from different threads at once (ctypes releases the GIL during
+    the calls).  Each thread has its own stream, weights, gradients and oracle;
+    both use a 2-wave occupancy cap, whose LDS slice above 64 KiB makes the
+    launcher raise the kernel's dynamic-LDS limit once per device -- the one
+    piece of state that contexts share."""
+    import threading
+    print("case: two host threads", flush=True)
+    K, k, W, steps = 3, 2, 1, 12
+    errors = []
+
+    def work(seed):
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                m = Model(SIZES, K, seed=seed)
+                ctx = B.Context(B.make_config(SIZES, K, k, W, 0.1, 0.9, 1e-4, stream=stream.cuda_stream,
+                                              waves_per_cu=2, cache_policy=B.SSD_CACHE_STREAMING), m.weights)
+                o = Oracle(m.w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=1e-4, mode="f32")
+                tables = [B.GradTable(g) for g in m.g_dev]
+                for it in range(steps):
+                    ctx.ssd_step(tables[it % 3])
+                    o.step(m.g_host[it % 3])
+                stream.synchronize()
+                compare_state(ctx, m, o, exact=True, where="thread %d" % seed)
+                ctx.close()
+        except BaseException as e:      # reported by the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(s,)) for s in (71, 72)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
