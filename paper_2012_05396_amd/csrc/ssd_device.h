@@ -29,6 +29,11 @@
 // over whole tiles, groups of 8, or groups of 2 and 4 without the look-ahead).
 constexpr int ssd_group_of(int K) { return K <= 8 ? K : 4; }
 constexpr bool ssd_prefetch_of(int K) { return K > 8; }
+// Cache policy bits of the streaming 128-bit stores: "sc1 nt" everywhere
+// (measured 1-2 % faster than plain "nt" for K = 1..14 and for the warm-up and
+// from-global kernels at any K) except in the plain steps-delay kernel at
+// K = 16, where "nt" alone measured 1 % faster in three sessions.
+constexpr bool ssd_store_sc1_of(int K, bool plain_delay) { return !(K == 16 && plain_delay); }
 
 enum { SSD_STAGE_WARMUP = 0, SSD_STAGE_DELAY = 2 };
 
@@ -212,7 +217,7 @@ template <bool NT> struct ssd_vec<1, NT> {
     {
         x[0] = NT ? __builtin_nontemporal_load(p) : *p;
     }
-    static __device__ __forceinline__ void st(gfloat *p, const float (&x)[1])
+    template <bool SC1 = true> static __device__ __forceinline__ void st(gfloat *p, const float (&x)[1])
     {
         if (NT)
             __builtin_nontemporal_store(x[0], p);
@@ -229,7 +234,7 @@ template <bool NT> struct ssd_vec<4, NT> {
         v4 v = NT ? __builtin_nontemporal_load((cgv4 *)p) : *(cgv4 *)p;
         x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
     }
-    static __device__ __forceinline__ void st(gfloat *p, const float (&x)[4])
+    template <bool SC1 = true> static __device__ __forceinline__ void st(gfloat *p, const float (&x)[4])
     {
         v4 v = {x[0], x[1], x[2], x[3]};
         if (!NT) {
@@ -237,12 +242,15 @@ template <bool NT> struct ssd_vec<4, NT> {
             return;
         }
         // "sc1 nt" (system-coherence bit + non-temporal) is a cache policy the
-        // compiler has no builtin for; measured 1-2 % faster than plain "nt"
-        // on MI355X.  The compiler cannot see into the asm, so the wait
+        // compiler has no builtin for; see ssd_store_sc1_of for where each
+        // form is used.  The compiler cannot see into the asm, so the wait
         // states that the ISA requires between a store of more than 64 bits
         // and a following VALU write of its data registers (2 on gfx950) are
         // supplied here: s_nop 1 idles for two cycles.
-        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+        if (SC1)
+            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+        else
+            asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
     }
 };
 

@@ -108,6 +108,7 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
 {
     typedef ssd_vec<VW, NT> V;
     constexpr int NG = (K + G - 1) / G;
+    constexpr bool SC1 = ssd_store_sc1_of(K, STAGE == SSD_STAGE_DELAY && !FG);
     ssd_group_regs<G, VW> cur = s.grp;
     float w[VW], S[VW], wn[VW], mn[VW];
     ssd_load_g<K, GD, G, NT, VW>(0, gp, e, cur);
@@ -132,15 +133,15 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
             // the whole tile is here: server update first, then nothing waits any more
 #pragma unroll
             for (int v = 0; v < VW; ++v) ssd_server_elem(S[v], w[v], s.mo[v], h, wn[v], mn[v]);
-            V::st(momp + e, mn);
-            V::st(wp + e, wn);
+            V::template st<SC1>(momp + e, mn);
+            V::template st<SC1>(wp + e, wn);
         }
         if (STAGE == SSD_STAGE_DELAY) {
             // FG: every w'_i is the global weight as it stood before this
             // iteration's server update (after a Pull, or at the end of warm-up),
             // which is in registers already; the w' arrays are not read.
             // Alg. 2: pre_weight takes w' as it was before this update.
-            if (j == 0 && PRE != SSD_PRE_KEEP) V::st(prep + e, FG ? w : cur.wl[0]);
+            if (j == 0 && PRE != SSD_PRE_KEEP) V::template st<SC1>(prep + e, FG ? w : cur.wl[0]);
 #pragma unroll
             for (int i = 0; i < G; ++i) {
                 if (j * G + i < K) {
@@ -151,7 +152,7 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
                         const float pv = (PRE == SSD_PRE_INIT) ? wli : s.p[v];
                         r[v] = ssd_glu_elem<XW>(cur.g[i][v], wli, pv, h);
                     }
-                    V::st(wlp + (int64_t)(j * G + i) * A + e, r);
+                    V::template st<SC1>(wlp + (int64_t)(j * G + i) * A + e, r);
                 }
             }
         }
@@ -165,8 +166,8 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
     if (NG > 1) {
 #pragma unroll
         for (int v = 0; v < VW; ++v) ssd_server_elem(S[v], w[v], s.mo[v], h, wn[v], mn[v]);
-        V::st(momp + e, mn);
-        V::st(wp + e, wn);
+        V::template st<SC1>(momp + e, mn);
+        V::template st<SC1>(wp + e, wn);
     }
 }
 
