@@ -153,6 +153,13 @@ def workload(name):
         if depth < 8 or (depth - 2) % 6:
             raise KeyError(name)
         return _wl(name, cifar_resnet((depth - 2) // 6), 8, 4, 20, grad_fan_in_scale=True, seed=108)
+    # one flat tensor of N elements, e.g. flat138357544: a model without layer
+    # structure, for sweeps (K = 8, k = 4)
+    if name.startswith("flat"):
+        n = int(name[len("flat"):])
+        if n < 1:
+            raise KeyError(name)
+        return _wl(name, [TensorSpec("flat.weight", (n,), "fc", 1024)], 8, 4, 20, seed=109)
     raise KeyError(name)
 
 
