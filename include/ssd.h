@@ -249,7 +249,9 @@ int ssd_worker_pull(ssd_ctx *ctx, int32_t worker);
  * flags return to their values at the start of the cycle, so each replay is
  * the next k iterations.  Replays do not advance the counters that
  * ssd_get_state reports, and the captured gradient sets must not be evicted
- * (use at most 8 distinct sets while the graph lives). */
+ * (use at most 8 distinct sets while the graph lives).  The hyper-parameters
+ * travel as kernel arguments, so a captured launch keeps the learning rates of
+ * the time of capture: capture again after ssd_set_lr. */
 int ssd_step(ssd_ctx *ctx, const void *const *const *grads);
 
 /* Write out the state that ssd_step only records: if w_local_is_global, copy
@@ -264,7 +266,9 @@ int ssd_materialize(ssd_ctx *ctx);
  * grad_sync = (pre_weight - w') * (1-m)/(lr*k)); lr_loc is loc_lr of
  * Eq. (glu-update).  The paper changes neither during a run; here both take
  * effect from the next call on, and the constant (1-m)/(lr*k) is formed
- * again from the new lr.  lr = 0 with delay_k > 0 is SSD_EINVAL. */
+ * again from the new lr.  lr = 0 with delay_k > 0 is SSD_EINVAL.  Enqueues
+ * nothing unless per-tensor multipliers are set (then one small upload), so a
+ * schedule may call it every iteration. */
 int ssd_set_lr(ssd_ctx *ctx, float lr, float lr_loc);
 
 /* Per-tensor multipliers, as optimisers of deep-learning frameworks keep them

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_glu_kernel(const ssd_glu_args a
     cgfloat *presrc = ssd_global(a.pre_src) + blk.ao;
     gfloat *predst = ssd_global(a.pre_dst) + blk.ao;
     const unsigned lo = blk.lo, len = blk.len, tid = threadIdx.x;
-    const ssd_hyper h = ssd_hyper_of(a.h, a.thyper[blk.tensor]);
+    const ssd_hyper h = a.thyper ? ssd_hyper_of(a.h, a.thyper[blk.tensor]) : a.h;
     if (vec) {
         // whole vectors from the lead-in (a multiple of 4 elements, see
         // ssd_tensor_desc) to the last whole vector, then the tail

@@ -128,7 +128,7 @@ struct ssd_fused_args {
     // then the K gradient pointers -- everything a wave needs about the
     // caller's arrays in one contiguous record
     const int64_t *rec;
-    const ssd_tensor_hyper *thyper; // [T]
+    const ssd_tensor_hyper *thyper; // [T], or NULL: the values in h hold for every tensor
     float *mom, *pre, *wl;
     int64_t A;                // elements per state array (worker stride)
     ssd_hyper h;              // per-tensor fields are replaced from thyper
@@ -147,7 +147,7 @@ struct ssd_glu_args {
     const float *pre_src;     // pre_weight array to read
     float *pre_dst;           // pre_weight array to write (init / refresh)
     float *wl;                // this worker's w'
-    const ssd_tensor_hyper *thyper; // [T]
+    const ssd_tensor_hyper *thyper; // [T], or NULL: the values in h hold for every tensor
     ssd_hyper h;              // per-tensor fields are replaced from thyper
 };
 

@@ -223,7 +223,8 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
 
     // block -> tensor -> one record {w, elem0, numel, g_0 .. g_{K-1}}
     // and the tensor's hyper-parameters
-    const ssd_hyper h = ssd_hyper_of(hglobal, thyper[t]);
+    // thyper == NULL: no tensor has multipliers, the global values hold for all
+    const ssd_hyper h = thyper ? ssd_hyper_of(hglobal, thyper[t]) : hglobal;
     const int64_t *rec = rec_table + (int64_t)t * (K + 3);
     float *w = reinterpret_cast<float *>(rec[0]);
     int64_t off;

@@ -313,6 +313,11 @@ struct ssd_ctx {
     // per-tensor hyper-parameters derived from them (device copy + two pinned
     // staging copies used in turn)
     std::vector<float> lr_mult, wd_mult;
+    // every multiplier is 1: the kernels take the global values from their
+    // arguments and the table is neither read nor kept up to date, so a
+    // learning-rate change costs no upload (schedules that change lr every
+    // iteration)
+    bool uniform_hyper = true;
     ssd_tensor_hyper *d_thyper = nullptr, *h_thyper[2] = {nullptr, nullptr};
     hipEvent_t thyper_ev[2] = {nullptr, nullptr};
     int thyper_next = 0;
@@ -762,7 +767,7 @@ static int launch_fused(ssd_ctx *c, int stage, int pre_action, int from_global)
     ssd_fused_args a;
     a.tab = c->tables();
     a.rec = rec;
-    a.thyper = c->d_thyper;
+    a.thyper = c->uniform_hyper ? nullptr : c->d_thyper;
     a.mom = c->mom;
     a.pre = c->pre[c->pre_cur];
     a.wl = c->wl;
@@ -936,7 +941,7 @@ static int ssd_worker_glu_update_impl(ssd_ctx *c, int32_t worker, const void *co
     a.pre_src = c->pre[c->pre_cur];
     a.pre_dst = c->pre[c->pre_cur ^ 1];
     a.wl = c->arr(c->wl, worker);
-    a.thyper = c->d_thyper;
+    a.thyper = c->uniform_hyper ? nullptr : c->d_thyper;
     a.h = c->h;
     e = ssd_launch_glu(c->cfg.grad_dtype, pre_action, (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the GLU kernel");
@@ -978,6 +983,7 @@ static int ssd_set_lr_impl(ssd_ctx *c, float lr, float lr_loc)
     c->h.lr = lr;
     c->h.lr_loc = lr_loc;
     c->set_c_sync();
+    if (c->uniform_hyper) return SSD_OK; // the new values travel as kernel arguments
     hipError_t e = c->upload_tensor_hyper();
     if (e != hipSuccess) return c->fail_hip(e, "upload of per-tensor hyper-parameters");
     return SSD_OK;
@@ -993,10 +999,14 @@ static int ssd_set_tensor_multipliers_impl(ssd_ctx *c, const float *lr_mult, con
     }
     DeviceGuard guard(c->cfg.device);
     if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
+    bool uniform = true;
     for (int t = 0; t < T; ++t) {
         c->lr_mult[t] = lr_mult ? lr_mult[t] : 1.0f;
         c->wd_mult[t] = wd_mult ? wd_mult[t] : 1.0f;
+        uniform = uniform && c->lr_mult[t] == 1.0f && c->wd_mult[t] == 1.0f;
     }
+    c->uniform_hyper = uniform;
+    if (uniform) return SSD_OK;
     hipError_t e = c->upload_tensor_hyper();
     if (e != hipSuccess) return c->fail_hip(e, "upload of per-tensor hyper-parameters");
     return SSD_OK;

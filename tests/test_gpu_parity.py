@@ -369,6 +369,36 @@ def test_two_stream_schedule_of_fig_3b():
     ctx.close()
 
 
+def test_multipliers_set_and_taken_back():
+    """Without multipliers the kernels take the hyper-parameters from their
+    arguments and ssd_set_lr uploads nothing; with multipliers they read the
+    per-tensor table.  Going there and back (all multipliers 1 again, or NULL)
+    with learning-rate changes on the way must leave the plain schedule's bits."""
+    print("case: multipliers set and taken back", flush=True)
+    from oracle.ssd_oracle import Oracle
+    from paper_2012_05396_amd import binding as B
+    numel, K, k, W = [3000, 257, 64], 3, 2, 1
+    model = Model(numel, K, seed=77)
+    ctx = B.Context(B.make_config(numel, K, k, W, 0.1, 0.9, 1e-3, stream=torch.cuda.current_stream().cuda_stream),
+                    model.weights)
+    o = Oracle(model.w0, K=K, k=k, W=W, lr=0.1, m=0.9, wd=1e-3, mode="f32")
+    ones = [1.0] * len(numel)
+    for it in range(W + 4 * k):
+        if it == 2:
+            ctx.ssd_set_tensor_multipliers(ones, ones)          # still uniform
+        if it == 3:
+            ctx.ssd_set_tensor_multipliers([1.0, 1.0, 1.0], [1.0, 1.0, 1.0 + 2.0 ** -23])
+            ctx.ssd_set_tensor_multipliers(None, None)          # the table was uploaded, and is dropped again
+        if it in (4, 6):
+            lr, lr_loc = (0.05, 0.3) if it == 4 else (0.2, 0.6)
+            ctx.ssd_set_lr(lr, lr_loc)
+            o.set_lr(lr, lr_loc)
+        ctx.ssd_step(model.g_dev[it % 3])
+        o.step(model.g_host[it % 3])
+        compare_state(ctx, model, o, exact=True, where="multipliers there and back it=%d" % it)
+    ctx.close()
+
+
 def test_per_tensor_multipliers_bit_exact():
     """lr / wd multipliers per tensor: every tensor must follow the oracle run
     with that tensor's own products (one binary32 multiplication each); a
