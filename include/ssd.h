@@ -195,8 +195,9 @@ int ssd_workspace_bytes(const ssd_config *cfg, size_t *bytes);
  *   workspace device memory of at least ssd_workspace_bytes, 256-byte
  *             aligned, owned by the caller, used exclusively by the context
  *             until ssd_destroy.
- * Enqueues the clearing of the momentum (and, if warmup_iters == 0 and
- * delay_k > 0, the copy w'_i = w_0).  On failure *out is NULL and
+ * Enqueues the clearing of the momentum and of the other state arrays (if
+ * warmup_iters == 0 and delay_k > 0, w'_i = w_0 is recorded, not copied: see
+ * ssd_state_view.w_local_is_global).  On failure *out is NULL and
  * ssd_last_error(NULL) has the reason. */
 int ssd_init(const ssd_config *cfg, float *const *weights, void *workspace,
              size_t workspace_bytes, ssd_ctx **out);
@@ -364,8 +365,9 @@ int ssd_lds_slice_bytes(int32_t waves_per_cu, int32_t lds_bytes_per_cu);
  * weights of that many workers, updates them, then goes on to the next group,
  * carrying the gradient sum in worker order), *prefetch whether the next
  * group's loads are requested before the current group's arithmetic.  Both
- * appear as the last two template arguments of ssd_fused_kernel in profiler
- * output.  Either pointer may be NULL. */
+ * appear as template arguments of ssd_fused_kernel in profiler output,
+ * followed by the last one, true for non-temporal accesses
+ * (ssd_state_view.streaming).  Either pointer may be NULL. */
 int ssd_fused_variant(int32_t num_workers, int32_t *group, int32_t *prefetch);
 
 /* Work chunk of the multi-tensor launch: `len` elements of tensor `tensor`
