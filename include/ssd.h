@@ -140,8 +140,14 @@ typedef struct {
  * whose weight pointer is 16-byte aligned does not start at the beginning of
  * its first block but ((address mod 1024) / 4) elements into it, so that the
  * 256-element tiles the kernels work on are aligned 1 KiB pieces of the
- * caller's arrays as well as of these.  Worker i's copy of a
- * per-worker array starts at base + i * arena_elems.  The pointers stay valid
+ * caller's arrays as well as of these.  Worker i's w_loc array starts at
+ * w_loc + i * arena_elems.  The K local-weight arrays w'_i are laid out block
+ * by block: arena element a of worker i is
+ *   w_local[i * w_local_worker_stride + (a / chunk_elems) * w_local_block_stride
+ *           + a % chunk_elems],
+ * which for up to 8 workers is the same planar form (strides arena_elems and
+ * chunk_elems) and for more workers puts the K copies of a block side by side
+ * (strides chunk_elems and K * chunk_elems).  The pointers stay valid
  * until ssd_destroy; the data they show are those of the work enqueued so
  * far (synchronise the stream before reading). */
 typedef struct {
@@ -159,6 +165,8 @@ typedef struct {
                                (SSD_CACHE_STREAMING), 0: ordinary ones         */
     int64_t num_chunks;
     int64_t arena_elems;
+    int64_t w_local_worker_stride; /* see above                               */
+    int64_t w_local_block_stride;
     const int64_t *tensor_offset; /* host [T], owned by the context           */
     float *mom;             /* device: momentum of the servers                */
     float *pre;             /* device: pre_weight (one copy: Sec. 3.3 says all

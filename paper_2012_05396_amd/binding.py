@@ -43,6 +43,7 @@ class ssd_state_view(C.Structure):
                 ("w_local_is_global", C.c_int32), ("w_loc_where", C.c_int32),
                 ("chunk_elems", C.c_int32), ("streaming", C.c_int32),
                 ("num_chunks", C.c_int64), ("arena_elems", C.c_int64),
+                ("w_local_worker_stride", C.c_int64), ("w_local_block_stride", C.c_int64),
                 ("tensor_offset", C.POINTER(C.c_int64)),
                 ("mom", C.c_void_p), ("pre", C.c_void_p),
                 ("w_local", C.c_void_p), ("w_loc", C.c_void_p)]
@@ -325,25 +326,31 @@ class Context:
         _check(lib.ssd_get_state(self.h, C.byref(v)), self.h)
         return v
 
-    # views of the library-owned state as torch tensors (no copies) --------
-    def _arena(self, ptr, count):
-        """float32 view of `count` consecutive state arrays starting at ptr;
-        they live inside self.workspace."""
-        v = self.ssd_get_state()
-        off = ptr - self.workspace.data_ptr()
-        assert off >= 0 and off % 4 == 0
-        A = v.arena_elems
-        flat = self.workspace[off:off + 4 * A * count].view(torch.float32)
-        return flat.view(count, A), v
-
-    def state_tensors(self, which, worker=None):
-        """List of T per-tensor views of a state array: which in {"mom",
-        "pre", "w_local", "w_loc"}; per-worker arrays need `worker`."""
+    # the library-owned state as torch tensors -------------------------------
+    def state_array(self, which, worker=None):
+        """One state array -- which in {"mom", "pre", "w_local", "w_loc"};
+        per-worker arrays need `worker` -- as a flat float32 tensor indexed by
+        arena element.  A view into the workspace, except for the local
+        weights of more than 8 workers, whose blocks are interleaved
+        (ssd_state_view.w_local_block_stride): those are gathered into a copy."""
         v = self.ssd_get_state()
         ptr = getattr(v, which)
         if ptr is None:
             raise SsdError(SSD_ESTATE, "state array %s does not exist (delay_k = 0)" % which)
+        off = ptr - self.workspace.data_ptr()
+        assert off >= 0 and off % 4 == 0
+        A, Ce, nb = v.arena_elems, v.chunk_elems, v.num_chunks
         count = self.K if which in ("w_local", "w_loc") else 1
-        arena, v = self._arena(ptr, count)
-        row = arena[worker if count > 1 else 0]
+        i = worker if count > 1 else 0
+        flat = self.workspace[off:off + 4 * A * count].view(torch.float32)
+        if which == "w_local" and v.w_local_block_stride != Ce:
+            blocks = flat.as_strided((nb, Ce), (v.w_local_block_stride, 1),
+                                     flat.storage_offset() + i * v.w_local_worker_stride)
+            return blocks.reshape(-1)
+        return flat[i * A:i * A + nb * Ce]
+
+    def state_tensors(self, which, worker=None):
+        """List of T per-tensor tensors of a state array (see state_array)."""
+        v = self.ssd_get_state()
+        row = self.state_array(which, worker)
         return [row[v.tensor_offset[t]:v.tensor_offset[t] + self.numel[t]] for t in range(self.T)]

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_glu_kernel(const ssd_glu_args a
     const bool vec = ssd_grad_aligned<GD>(g);
     typedef typename ssd_gvec<GD, 4>::ptr gptr;
     const gptr gp = (gptr)g + blk.off;
-    gfloat *wlp = ssd_global(a.wl) + blk.ao;
+    gfloat *wlp = ssd_global(a.wl) + (int64_t)blockIdx.x * a.wl_block_stride;
     cgfloat *presrc = ssd_global(a.pre_src) + blk.ao;
     gfloat *predst = ssd_global(a.pre_dst) + blk.ao;
     const unsigned lo = blk.lo, len = blk.len, tid = threadIdx.x;
@@ -96,7 +96,8 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_pull_kernel(const ssd_pull_args
     const ssd_block blk = ssd_locate(a.tab, blockIdx.x, td);
     const bool vec = ssd_aligned16(td.w);
     cgfloat *wp = ssd_global((const float *)td.w) + blk.off;
-    gfloat *wlp = ssd_global(a.wl) + blk.ao, *wlocp = ssd_global(a.wloc) + blk.ao;
+    gfloat *wlp = ssd_global(a.wl) + (int64_t)blockIdx.x * a.wl_block_stride;
+    gfloat *wlocp = ssd_global(a.wloc) + blk.ao;
     const unsigned lo = blk.lo, len = blk.len, tid = threadIdx.x;
     if (vec) {
         const unsigned len4 = lo + ((len - lo) & ~3u);

@@ -29,11 +29,15 @@
 // over whole tiles, groups of 8, or groups of 2 and 4 without the look-ahead).
 constexpr int ssd_group_of(int K) { return K <= 8 ? K : 4; }
 constexpr bool ssd_prefetch_of(int K) { return K > 8; }
-// Cache policy bits of the streaming 128-bit stores: "sc1 nt" everywhere
-// (measured 1-2 % faster than plain "nt" for K = 1..14 and for the warm-up and
-// from-global kernels at any K) except in the plain steps-delay kernel at
-// K = 16, where "nt" alone measured 1 % faster in three sessions.
-constexpr bool ssd_store_sc1_of(int K, bool plain_delay) { return !(K == 16 && plain_delay); }
+// Layout of the K local-weight arrays w'_i.  Planar (K <= 8): worker i's array
+// is one arena, the arrays follow each other.  Interleaved (K > 8): block b of
+// worker i is at ((b * K + i) * C), so the K tiles a wave needs lie in one
+// K KiB piece instead of K places a whole array apart -- with 2K+3 streams
+// the address translations of a compute unit no longer hold one entry per
+// stream (hit rate 85 % at K = 16), and this takes K-1 streams away: +2 % to
+// +4 % on the plain kernel for K = 9 ... 16 against planar arrays.  At K = 8, where translation hits 99.7 % anyway
+// and a wave asks for all 8 tiles at once, the same layout measured 2 % slower.
+constexpr bool ssd_interleave_of(int K) { return K > 8; }
 
 enum { SSD_STAGE_WARMUP = 0, SSD_STAGE_DELAY = 2 };
 
@@ -130,7 +134,7 @@ struct ssd_fused_args {
     const int64_t *rec;
     const ssd_tensor_hyper *thyper; // [T], or NULL: the values in h hold for every tensor
     float *mom, *pre, *wl;
-    int64_t A;                // elements per state array (worker stride)
+    int64_t A;                // elements per planar state array
     ssd_hyper h;              // per-tensor fields are replaced from thyper
 };
 
@@ -146,14 +150,16 @@ struct ssd_glu_args {
     const void *const *gptr;  // [T] gradient pointers of the one worker
     const float *pre_src;     // pre_weight array to read
     float *pre_dst;           // pre_weight array to write (init / refresh)
-    float *wl;                // this worker's w'
+    float *wl;                // this worker's w': its copy of block 0
+    int64_t wl_block_stride;  // elements from its copy of block b to that of block b+1
     const ssd_tensor_hyper *thyper; // [T], or NULL: the values in h hold for every tensor
     ssd_hyper h;              // per-tensor fields are replaced from thyper
 };
 
 struct ssd_pull_args {
     ssd_tables tab;
-    float *wl, *wloc;         // this worker's arrays
+    float *wl, *wloc;         // this worker's arrays (wl: its copy of block 0)
+    int64_t wl_block_stride;  // as in ssd_glu_args; w_loc arrays are always planar
 };
 
 static __device__ __forceinline__ ssd_block ssd_locate(const ssd_tables &tab, unsigned b,
@@ -217,7 +223,7 @@ template <bool NT> struct ssd_vec<1, NT> {
     {
         x[0] = NT ? __builtin_nontemporal_load(p) : *p;
     }
-    template <bool SC1 = true> static __device__ __forceinline__ void st(gfloat *p, const float (&x)[1])
+    static __device__ __forceinline__ void st(gfloat *p, const float (&x)[1])
     {
         if (NT)
             __builtin_nontemporal_store(x[0], p);
@@ -234,7 +240,7 @@ template <bool NT> struct ssd_vec<4, NT> {
         v4 v = NT ? __builtin_nontemporal_load((cgv4 *)p) : *(cgv4 *)p;
         x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
     }
-    template <bool SC1 = true> static __device__ __forceinline__ void st(gfloat *p, const float (&x)[4])
+    static __device__ __forceinline__ void st(gfloat *p, const float (&x)[4])
     {
         v4 v = {x[0], x[1], x[2], x[3]};
         if (!NT) {
@@ -242,15 +248,12 @@ template <bool NT> struct ssd_vec<4, NT> {
             return;
         }
         // "sc1 nt" (system-coherence bit + non-temporal) is a cache policy the
-        // compiler has no builtin for; see ssd_store_sc1_of for where each
-        // form is used.  The compiler cannot see into the asm, so the wait
+        // compiler has no builtin for; measured 1-2 % faster than plain "nt"
+        // on MI355X.  The compiler cannot see into the asm, so the wait
         // states that the ISA requires between a store of more than 64 bits
         // and a following VALU write of its data registers (2 on gfx950) are
         // supplied here: s_nop 1 idles for two cycles.
-        if (SC1)
-            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
-        else
-            asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
     }
 };
 

@@ -62,13 +62,13 @@ template <int G, int VW> struct ssd_head_regs {
 };
 
 template <int K, int STAGE, bool FG, int G, bool NT, int VW>
-__device__ __forceinline__ void ssd_load_wl(int j, gfloat *wlp, int64_t A, unsigned e,
+__device__ __forceinline__ void ssd_load_wl(int j, gfloat *wlp, int64_t WS, unsigned e,
                                             ssd_group_regs<G, VW> &r)
 {
     if (STAGE == SSD_STAGE_DELAY && !FG) {
 #pragma unroll
         for (int i = 0; i < G; ++i)
-            if (j * G + i < K) ssd_vec<VW, NT>::ld(wlp + (int64_t)(j * G + i) * A + e, r.wl[i]);
+            if (j * G + i < K) ssd_vec<VW, NT>::ld(wlp + (int64_t)(j * G + i) * WS + e, r.wl[i]);
     }
 }
 
@@ -82,13 +82,13 @@ __device__ __forceinline__ void ssd_load_g(int j, const typename ssd_gvec<GD, 4>
 }
 
 template <int K, int STAGE, int PRE, bool FG, int G, bool NT, int VW>
-__device__ __forceinline__ void ssd_load_head(gfloat *momp, gfloat *prep, gfloat *wlp, int64_t A, unsigned e,
+__device__ __forceinline__ void ssd_load_head(gfloat *momp, gfloat *prep, gfloat *wlp, int64_t WS, unsigned e,
                                               ssd_head_regs<G, VW> &s)
 {
     ssd_vec<VW, NT>::ld(momp + e, s.mo);
     if (STAGE == SSD_STAGE_DELAY) {
         if (PRE != SSD_PRE_INIT) ssd_vec<VW, NT>::ld(prep + e, s.p);
-        ssd_load_wl<K, STAGE, FG, G, NT, VW>(0, wlp, A, e, s.grp);
+        ssd_load_wl<K, STAGE, FG, G, NT, VW>(0, wlp, WS, e, s.grp);
     }
 }
 
@@ -103,12 +103,11 @@ __device__ __forceinline__ void ssd_load_head(gfloat *momp, gfloat *prep, gfloat
 // arithmetic on early ones (16-bit gradient kernels: 5.85 instead of 6.39 TB/s).
 template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF, bool NT, int VW>
 __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ssd_gvec<GD, 4>::ptr (&gp)[K],
-                                           gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t A,
+                                           gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t WS,
                                            unsigned e, const ssd_head_regs<G, VW> &s)
 {
     typedef ssd_vec<VW, NT> V;
     constexpr int NG = (K + G - 1) / G;
-    constexpr bool SC1 = ssd_store_sc1_of(K, STAGE == SSD_STAGE_DELAY && !FG);
     ssd_group_regs<G, VW> cur = s.grp;
     float w[VW], S[VW], wn[VW], mn[VW];
     ssd_load_g<K, GD, G, NT, VW>(0, gp, e, cur);
@@ -118,7 +117,7 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
     for (int j = 0; j < NG; ++j) {
         ssd_group_regs<G, VW> nxt = {};
         if (PF && j + 1 < NG) {
-            ssd_load_wl<K, STAGE, FG, G, NT, VW>(j + 1, wlp, A, e, nxt);
+            ssd_load_wl<K, STAGE, FG, G, NT, VW>(j + 1, wlp, WS, e, nxt);
             ssd_load_g<K, GD, G, NT, VW>(j + 1, gp, e, nxt);
         }
         // Eq. (server): the sum of the K gradients, in worker order
@@ -133,15 +132,15 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
             // the whole tile is here: server update first, then nothing waits any more
 #pragma unroll
             for (int v = 0; v < VW; ++v) ssd_server_elem(S[v], w[v], s.mo[v], h, wn[v], mn[v]);
-            V::template st<SC1>(momp + e, mn);
-            V::template st<SC1>(wp + e, wn);
+            V::st(momp + e, mn);
+            V::st(wp + e, wn);
         }
         if (STAGE == SSD_STAGE_DELAY) {
             // FG: every w'_i is the global weight as it stood before this
             // iteration's server update (after a Pull, or at the end of warm-up),
             // which is in registers already; the w' arrays are not read.
             // Alg. 2: pre_weight takes w' as it was before this update.
-            if (j == 0 && PRE != SSD_PRE_KEEP) V::template st<SC1>(prep + e, FG ? w : cur.wl[0]);
+            if (j == 0 && PRE != SSD_PRE_KEEP) V::st(prep + e, FG ? w : cur.wl[0]);
 #pragma unroll
             for (int i = 0; i < G; ++i) {
                 if (j * G + i < K) {
@@ -152,12 +151,12 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
                         const float pv = (PRE == SSD_PRE_INIT) ? wli : s.p[v];
                         r[v] = ssd_glu_elem<XW>(cur.g[i][v], wli, pv, h);
                     }
-                    V::template st<SC1>(wlp + (int64_t)(j * G + i) * A + e, r);
+                    V::st(wlp + (int64_t)(j * G + i) * WS + e, r);
                 }
             }
         }
         if (!PF && j + 1 < NG) {
-            ssd_load_wl<K, STAGE, FG, G, NT, VW>(j + 1, wlp, A, e, nxt);
+            ssd_load_wl<K, STAGE, FG, G, NT, VW>(j + 1, wlp, WS, e, nxt);
             ssd_load_g<K, GD, G, NT, VW>(j + 1, gp, e, nxt);
         }
         if (j + 1 < NG) cur = nxt;
@@ -166,8 +165,8 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
     if (NG > 1) {
 #pragma unroll
         for (int v = 0; v < VW; ++v) ssd_server_elem(S[v], w[v], s.mo[v], h, wn[v], mn[v]);
-        V::template st<SC1>(momp + e, mn);
-        V::template st<SC1>(wp + e, wn);
+        V::st(momp + e, mn);
+        V::st(wp + e, wn);
     }
 }
 
@@ -178,12 +177,12 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
 // cases with the head state preloaded in `s`.
 template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF, bool NT>
 __device__ __forceinline__ void ssd_tile(const ssd_hyper &h, const typename ssd_gvec<GD, 4>::ptr (&gp)[K],
-                                         gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t A,
+                                         gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t WS,
                                          unsigned e0, unsigned lo, unsigned len, bool vec,
                                          const ssd_head_regs<G, 4> &s)
 {
     if (vec && e0 >= lo && e0 + 3 < len) {
-        ssd_finish<K, GD, STAGE, PRE, FG, XW, G, PF, NT, 4>(h, gp, wp, momp, prep, wlp, A, e0, s);
+        ssd_finish<K, GD, STAGE, PRE, FG, XW, G, PF, NT, 4>(h, gp, wp, momp, prep, wlp, WS, e0, s);
     } else if (e0 + 3 >= lo && e0 < len) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -193,7 +192,7 @@ __device__ __forceinline__ void ssd_tile(const ssd_hyper &h, const typename ssd_
                 s1.p[0] = s.p[v];
 #pragma unroll
                 for (int i = 0; i < G; ++i) s1.grp.wl[i][0] = s.grp.wl[i][v];
-                ssd_finish<K, GD, STAGE, PRE, FG, XW, G, false, NT, 1>(h, gp, wp, momp, prep, wlp, A, e0 + v, s1);
+                ssd_finish<K, GD, STAGE, PRE, FG, XW, G, false, NT, 1>(h, gp, wp, momp, prep, wlp, WS, e0 + v, s1);
             }
         }
     }
@@ -217,9 +216,12 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
     // padded to whole blocks, so the first tile is requested right away
     const int64_t ao = (int64_t)blockIdx.x * C;
     gfloat *momp = ssd_global(mom) + ao, *prep = ssd_global(pre) + ao;
-    gfloat *wlp = ssd_global(wl) + ao;
+    // local weights: planar arrays A apart, or the K copies of a block side by side
+    constexpr bool IL = ssd_interleave_of(K);
+    gfloat *wlp = ssd_global(wl) + (IL ? ao * K : ao);
+    const int64_t WS = IL ? (int64_t)C : A; // from worker i's copy of the block to worker i+1's
     ssd_head_regs<G, 4> s;
-    ssd_load_head<K, STAGE, PRE, FG, G, NT, 4>(momp, prep, wlp, A, lane * 4, s);
+    ssd_load_head<K, STAGE, PRE, FG, G, NT, 4>(momp, prep, wlp, WS, lane * 4, s);
 
     // block -> tensor -> one record {w, elem0, numel, g_0 .. g_{K-1}}
     // and the tensor's hyper-parameters
@@ -243,10 +245,10 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
 
     unsigned base = 0;
     for (;;) {
-        ssd_tile<K, GD, STAGE, PRE, FG, XW, G, PF, NT>(h, gp, wp, momp, prep, wlp, A, base + lane * 4, lo, len, vec, s);
+        ssd_tile<K, GD, STAGE, PRE, FG, XW, G, PF, NT>(h, gp, wp, momp, prep, wlp, WS, base + lane * 4, lo, len, vec, s);
         base += SSD_BLOCK * 4;
         if (base >= len) break; // uniform
-        ssd_load_head<K, STAGE, PRE, FG, G, NT, 4>(momp, prep, wlp, A, base + lane * 4, s);
+        ssd_load_head<K, STAGE, PRE, FG, G, NT, 4>(momp, prep, wlp, WS, base + lane * 4, s);
     }
 }
 

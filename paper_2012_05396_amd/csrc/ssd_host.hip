@@ -402,6 +402,11 @@ struct ssd_ctx {
     }
     float *arr(float *base, int i) const { return base + (int64_t)i * stride_elems(); }
     int64_t stride_elems() const { return L.stride; }
+    // w'_i: the K local-weight arrays are planar or interleaved by block (ssd_interleave_of)
+    bool interleaved() const { return ssd_interleave_of(cfg.num_workers); }
+    int64_t wl_worker_stride() const { return interleaved() ? L.chunk_elems : L.stride; }
+    int64_t wl_block_stride() const { return interleaved() ? (int64_t)cfg.num_workers * L.chunk_elems : L.chunk_elems; }
+    float *wl_of(int i) const { return wl + (int64_t)i * wl_worker_stride(); }
 };
 
 extern "C" {
@@ -728,14 +733,14 @@ static int check_grads(ssd_ctx *c, const void *const *const *grads)
 // Beyond K = 8 a wave takes the workers in groups of 4, two groups requested
 // at a time, so its loads in flight no longer grow with K; measured at K = 9,
 // 10, 12, 14, 16: 4 waves for the plain kernel (5 at K = 9), 6 for the
-// from-global (5 at K = 16: +2 % in three sessions) and the warm-up kernel
-// (which have no local weights to read, so half the loads in flight); with
-// 16-bit gradients (half-size gradient loads; K = 16) 5, 6 and 8.
+// from-global and the warm-up kernel (which have no local weights to read, so
+// half the loads in flight); with 16-bit gradients (half-size gradient loads;
+// K = 16) 5, 6 and 8.
 static int default_waves_per_cu(int K, int stage, int from_global, bool grad16)
 {
     if (K > 8) {
         if (stage == SSD_STAGE_WARMUP) return grad16 ? 8 : 6;
-        if (from_global) return (K == 16 && !grad16) ? 5 : 6;
+        if (from_global) return 6;
         return (grad16 || K == 9) ? 5 : 4;
     }
     int loads2, budget, floor_n; // loads per lane in halves of a 128-bit load
@@ -799,7 +804,7 @@ static int materialize(ssd_ctx *c)
     if (!c->wl_is_global) return SSD_OK;
     const int K = c->cfg.num_workers;
     for (int i = 0; i < K; ++i) {
-        ssd_pull_args a = {c->tables(), c->arr(c->wl, i), c->arr(c->wloc, i)};
+        ssd_pull_args a = {c->tables(), c->wl_of(i), c->arr(c->wloc, i), c->wl_block_stride()};
         hipError_t e = ssd_launch_pull(c->wl_holds_wloc ? 0 : 1, (unsigned)c->L.num_chunks, c->stream, a);
         if (e != hipSuccess) return c->fail_hip(e, "launch of the pull kernel");
         c->wloc_fresh[i] = 1;
@@ -940,7 +945,8 @@ static int ssd_worker_glu_update_impl(ssd_ctx *c, int32_t worker, const void *co
     a.gptr = reinterpret_cast<const void *const *>(tab);
     a.pre_src = c->pre[c->pre_cur];
     a.pre_dst = c->pre[c->pre_cur ^ 1];
-    a.wl = c->arr(c->wl, worker);
+    a.wl = c->wl_of(worker);
+    a.wl_block_stride = c->wl_block_stride();
     a.thyper = c->uniform_hyper ? nullptr : c->d_thyper;
     a.h = c->h;
     e = ssd_launch_glu(c->cfg.grad_dtype, pre_action, (unsigned)c->L.num_chunks, c->stream, a);
@@ -965,7 +971,7 @@ static int ssd_worker_pull_impl(ssd_ctx *c, int32_t worker)
     if (!guard.ok) return c->fail(SSD_EHIP, "cannot select device %d", c->cfg.device);
     int rc = materialize(c);
     if (rc != SSD_OK) return rc;
-    ssd_pull_args a = {c->tables(), c->arr(c->wl, worker), c->arr(c->wloc, worker)};
+    ssd_pull_args a = {c->tables(), c->wl_of(worker), c->arr(c->wloc, worker), c->wl_block_stride()};
     hipError_t e = ssd_launch_pull(c->has_local[worker] ? 0 : 1, (unsigned)c->L.num_chunks, c->stream, a);
     if (e != hipSuccess) return c->fail_hip(e, "launch of the pull kernel");
     c->has_local[worker] = 1;
@@ -1044,6 +1050,8 @@ int ssd_get_state(ssd_ctx *c, ssd_state_view *out)
     out->streaming = c->streaming ? 1 : 0;
     out->num_chunks = c->L.num_chunks;
     out->arena_elems = c->stride_elems();
+    out->w_local_worker_stride = c->wl_worker_stride();
+    out->w_local_block_stride = c->wl_block_stride();
     out->tensor_offset = c->L.tensor_offset.data();
     out->mom = c->mom;
     out->pre = c->pre[c->pre_cur];

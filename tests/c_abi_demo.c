@@ -138,8 +138,15 @@ int main(void)
         CK(hipMemcpy(buf, v.pre + v.tensor_offset[t], sizeof(float) * numel[t], hipMemcpyDeviceToHost));
         bad += memcmp(buf, o.pre + off[t], sizeof(float) * numel[t]) != 0;
         for (int i = 0; i < K; ++i) {
-            CK(hipMemcpy(buf, v.w_local + i * v.arena_elems + v.tensor_offset[t], sizeof(float) * numel[t],
-                         hipMemcpyDeviceToHost));
+            /* w'_i block by block: the general addressing of ssd_state_view (planar for this K) */
+            for (int64_t a = v.tensor_offset[t], end = a + numel[t]; a < end;) {
+                const int64_t blk = a / v.chunk_elems, pos = a % v.chunk_elems;
+                const int64_t n = end - a < v.chunk_elems - pos ? end - a : v.chunk_elems - pos;
+                CK(hipMemcpy(buf + (a - v.tensor_offset[t]),
+                             v.w_local + i * v.w_local_worker_stride + blk * v.w_local_block_stride + pos,
+                             sizeof(float) * n, hipMemcpyDeviceToHost));
+                a += n;
+            }
             bad += memcmp(buf, o.wl + i * N + off[t], sizeof(float) * numel[t]) != 0;
         }
     }

@@ -98,11 +98,7 @@ def run_full(name, piecewise_check=False, wl=None, grad_dtype=0, tol_elem=1e-5):
         ctx2 = B.Context(mk(), workloads.views(w2, wl.tensors, offs))
 
     def arena(which, worker=0):
-        vv = ctx.ssd_get_state()
-        ptr = getattr(vv, which)
-        count = K if which in ("w_local", "w_loc") else 1
-        a, _ = ctx._arena(ptr, count)
-        return a[worker]
+        return ctx.state_array(which, worker)
 
     def check(it):
         """Compare the sample with both oracles, and whole-array properties."""
@@ -180,13 +176,13 @@ def run_full(name, piecewise_check=False, wl=None, grad_dtype=0, tol_elem=1e-5):
         for which, cnt in (("mom", 1), ("pre", 1), ("w_local", K)):
             if k == 0 and which != "mom":
                 continue
-            a, _ = ctx._arena(getattr(va, which), cnt)
-            b, _ = ctx2._arena(getattr(vb, which), cnt)
-            for t in range(T):
-                # each context has its own arena offsets (they follow its weight pointers)
-                sa = slice(va.tensor_offset[t], va.tensor_offset[t] + numel[t])
-                sb = slice(vb.tensor_offset[t], vb.tensor_offset[t] + numel[t])
-                assert torch.equal(a[:, sa].view(torch.int32), b[:, sb].view(torch.int32)), (name, which, t)
+            for i in range(cnt):
+                a, b = ctx.state_array(which, i), ctx2.state_array(which, i)
+                for t in range(T):
+                    # each context has its own arena offsets (they follow its weight pointers)
+                    sa = slice(va.tensor_offset[t], va.tensor_offset[t] + numel[t])
+                    sb = slice(vb.tensor_offset[t], vb.tensor_offset[t] + numel[t])
+                    assert torch.equal(a[sa].view(torch.int32), b[sb].view(torch.int32)), (name, which, i, t)
     ctx.close()
     if ctx2 is not None:
         ctx2.close()
