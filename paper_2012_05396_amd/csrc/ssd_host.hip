@@ -232,8 +232,8 @@ int64_t lead_of(const float *w, int64_t numel)
 // (MI355X: 256 MiB of memory-side cache; HIP reports no such figure).  Then the
 // arrays are still cached when the next iteration comes, provided the accesses
 // are not marked non-temporal.  Measured on MI355X with K = 1..16 on 0.27 M-
-// to 14 M-element models: ordinary accesses are 4-22 % faster up to 280 MB
-// touched per iteration, equal at 307 MB and 10-14 % slower from 487 MB on.
+// to 25 M-element models: ordinary accesses are 4-27 % faster up to about
+// 300 MB touched per iteration and 10-23 % slower from 490 MB on.
 constexpr size_t kLastLevelCacheBytes = (size_t)256 << 20;
 
 bool fits_last_level_cache(const ssd_config &c, const Layout &L)
