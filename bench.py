@@ -84,10 +84,8 @@ def read_profile(path):
 def dominant_kernel_name(B, K, gd, streaming=True):
     """Name of the plain steps-delay kernel as rocprofv3 prints it: template
     arguments K, gradient element type, stage, pre_weight action, from_global,
-    exact_w_minus, workers per group, prefetch, non-temporal accesses."""
-    G, PF = B.ssd_fused_variant(K)
-    return "ssd_fused_kernel<%d, %d, 2, 0, false, false, %d, %s, %s>" % (
-        K, gd, G, "true" if PF else "false", "true" if streaming else "false")
+    exact_w_minus, non-temporal accesses."""
+    return "ssd_fused_kernel<%d, %d, 2, 0, false, false, %s>" % (K, gd, "true" if streaming else "false")
 
 
 def variant_name(kind, pa, fg):

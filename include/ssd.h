@@ -368,16 +368,6 @@ int ssd_step_kind_of(int64_t iteration, int32_t warmup_iters, int32_t delay_k,
  * positive multiple of 128. */
 int ssd_lds_slice_bytes(int32_t waves_per_cu, int32_t lds_bytes_per_cu);
 
-/* How the fused kernel for K = num_workers is built: *group receives the number
- * of workers a wave takes at a time (it requests the gradients and local
- * weights of that many workers, updates them, then goes on to the next group,
- * carrying the gradient sum in worker order), *prefetch whether the next
- * group's loads are requested before the current group's arithmetic.  Both
- * appear as template arguments of ssd_fused_kernel in profiler output,
- * followed by the last one, true for non-temporal accesses
- * (ssd_state_view.streaming).  Either pointer may be NULL. */
-int ssd_fused_variant(int32_t num_workers, int32_t *group, int32_t *prefetch);
-
 /* Work chunk of the multi-tensor launch: `len` elements of tensor `tensor`
  * starting at element `offset` of that tensor. */
 typedef struct {

@@ -63,7 +63,6 @@ def _load():
     sigs = {
         "ssd_config_defaults": (C.c_int, [P(ssd_config), C.c_int32, C.c_float, C.c_float]),
         "ssd_lds_slice_bytes": (C.c_int, [C.c_int32, C.c_int32]),
-        "ssd_fused_variant": (C.c_int, [C.c_int32, P(C.c_int32), P(C.c_int32)]),
         "ssd_workspace_bytes": (C.c_int, [P(ssd_config), P(C.c_size_t)]),
         "ssd_init": (C.c_int, [P(ssd_config), P(C.c_void_p), C.c_void_p, C.c_size_t, P(C.c_void_p)]),
         "ssd_server_aggregate_update": (C.c_int, [C.c_void_p, P(C.c_void_p)]),
@@ -164,15 +163,6 @@ def ssd_lds_slice_bytes(waves_per_cu, lds_bytes_per_cu):
     if n < 0:
         raise SsdError(n, "bad argument")
     return n
-
-
-def ssd_fused_variant(K):
-    """(workers per group, prefetch) of the fused kernel for K workers."""
-    g, pf = C.c_int32(0), C.c_int32(0)
-    rc = lib.ssd_fused_variant(K, C.byref(g), C.byref(pf))
-    if rc != SSD_OK:
-        raise SsdError(rc, "bad argument")
-    return g.value, bool(pf.value)
 
 
 def make_config(numel, K, k, W, lr, momentum, wd, lr_loc=None, alpha=None, beta=None, wd_loc=None,

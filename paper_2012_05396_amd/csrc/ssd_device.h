@@ -22,20 +22,14 @@
 #define SSD_BLOCK 64
 #define SSD_COPY_BLOCK 256
 
-// Workers per group of the fused kernel (see ssd_fused.hip) and whether the
-// next group's loads are requested before the current group's arithmetic.
-// Up to 8 workers a wave takes the whole tile at once; beyond that, groups of
-// 4 with the next group requested ahead measured best on MI355X (K = 16: +2 %
-// over whole tiles, groups of 8, or groups of 2 and 4 without the look-ahead).
-constexpr int ssd_group_of(int K) { return K <= 8 ? K : 4; }
-constexpr bool ssd_prefetch_of(int K) { return K > 8; }
 // Layout of the K local-weight arrays w'_i.  Planar (K <= 8): worker i's array
 // is one arena, the arrays follow each other.  Interleaved (K > 8): block b of
 // worker i is at ((b * K + i) * C), so the K tiles a wave needs lie in one
 // K KiB piece instead of K places a whole array apart -- with 2K+3 streams
 // the address translations of a compute unit no longer hold one entry per
-// stream (hit rate 85 % at K = 16), and this takes K-1 streams away: +2 % to
-// +4 % on the plain kernel for K = 9 ... 16 against planar arrays.  At K = 8, where translation hits 99.7 % anyway
+// stream (hit rate 85 % at K = 16), and this takes K-1 streams away: the plain
+// kernel gains 5-8 % for K = 9 ... 16 against planar arrays (both at their
+// best number of resident waves).  At K = 8, where translation hits 99.7 % anyway
 // and a wave asks for all 8 tiles at once, the same layout measured 2 % slower.
 constexpr bool ssd_interleave_of(int K) { return K > 8; }
 

@@ -11,27 +11,18 @@
 // global weight, so the host only records that fact and the next launch
 // (template flag FG) takes w'_i from the global weight it loads anyway.
 //
-// Workers in groups.  A wave does not request all 2K+3 arrays of its tile at
-// once: it takes the workers in groups of G (template argument; ssd_group_of).
-// For group j it needs g_i and w'_i of the G workers of the group only; the
-// GLU update of worker i depends on nothing else that changes, and the sum of
-// the gradients is carried from group to group in worker order, so the
-// rounding sequence S = g_0; S = S + g_i (i = 1..K-1) is the same as without
-// groups.  That bounds the loads a wave has in flight by the group size, not
-// by K: the best HBM throughput of this many-stream access pattern on MI355X
-// is reached with a nearly constant number of loads in flight per compute
-// unit, whatever K is, and with K = 16 a whole-tile wave overshoots it.
-// With PF the loads of group j+1 are requested before the arithmetic and the
-// stores of group j.
-//
 // Order of issue inside a wave: the loads of the library's own state (momentum,
-// pre_weight, the first group's local weights) need nothing but blockIdx, so
-// they go out first; the two table lookups that lead to the caller's pointers
-// (block -> tensor, tensor -> one record with the weight and K gradient
-// pointers) overlap with them; then the first group's gradient loads and the
-// weight load; then, group by group, arithmetic and stores.  128-bit accesses
-// whenever every caller pointer of the tensor is 16-byte aligned, else element
-// by element.
+// pre_weight, the K local weights) need nothing but blockIdx, so they go out
+// first; the two table lookups that lead to the caller's pointers (block ->
+// tensor, tensor -> one record with the weight and K gradient pointers)
+// overlap with them; then the K gradient loads and the weight load; then
+// arithmetic and stores.  A wave asks for its whole tile at once, 2K+3 loads
+// per lane; how many waves a compute unit holds is capped by the host
+// (ssd_lds_slice_bytes).  128-bit accesses whenever every caller pointer of the
+// tensor is 16-byte aligned, else element by element.
+//
+// The K local weights of a block are K arrays a whole arena apart (K <= 8) or
+// lie side by side (K > 8), see ssd_interleave_of.
 //
 // NT selects the marking of every global access: non-temporal for models
 // that stream through HBM, ordinary for models whose arrays stay in the
@@ -50,123 +41,73 @@
 #error "compile with -DSSD_GD=<ssd_grad_dtype of the gradient buffers>"
 #endif
 
-// registers of one group of workers: their local weights and gradients
-template <int G, int VW> struct ssd_group_regs {
-    float wl[G][VW], g[G][VW];
-};
-
 // state of the tile that is requested before the table lookups return
-template <int G, int VW> struct ssd_head_regs {
-    float mo[VW], p[VW];
-    ssd_group_regs<G, VW> grp; // .wl of group 0
+template <int K, int VW> struct ssd_head_regs {
+    float mo[VW], p[VW], wl[K][VW];
 };
 
-template <int K, int STAGE, bool FG, int G, bool NT, int VW>
-__device__ __forceinline__ void ssd_load_wl(int j, gfloat *wlp, int64_t WS, unsigned e,
-                                            ssd_group_regs<G, VW> &r)
-{
-    if (STAGE == SSD_STAGE_DELAY && !FG) {
-#pragma unroll
-        for (int i = 0; i < G; ++i)
-            if (j * G + i < K) ssd_vec<VW, NT>::ld(wlp + (int64_t)(j * G + i) * WS + e, r.wl[i]);
-    }
-}
-
-template <int K, int GD, int G, bool NT, int VW>
-__device__ __forceinline__ void ssd_load_g(int j, const typename ssd_gvec<GD, 4>::ptr (&gp)[K], unsigned e,
-                                           ssd_group_regs<G, VW> &r)
-{
-#pragma unroll
-    for (int i = 0; i < G; ++i)
-        if (j * G + i < K) ssd_gvec<GD, VW, NT>::ld(gp[j * G + i] + e, r.g[i]);
-}
-
-template <int K, int STAGE, int PRE, bool FG, int G, bool NT, int VW>
+template <int K, int STAGE, int PRE, bool FG, bool NT, int VW>
 __device__ __forceinline__ void ssd_load_head(gfloat *momp, gfloat *prep, gfloat *wlp, int64_t WS, unsigned e,
-                                              ssd_head_regs<G, VW> &s)
+                                              ssd_head_regs<K, VW> &s)
 {
     ssd_vec<VW, NT>::ld(momp + e, s.mo);
     if (STAGE == SSD_STAGE_DELAY) {
         if (PRE != SSD_PRE_INIT) ssd_vec<VW, NT>::ld(prep + e, s.p);
-        ssd_load_wl<K, STAGE, FG, G, NT, VW>(0, wlp, WS, e, s.grp);
+        if (!FG) {
+#pragma unroll
+            for (int i = 0; i < K; ++i) ssd_vec<VW, NT>::ld(wlp + (int64_t)i * WS + e, s.wl[i]);
+        }
     }
 }
 
 // Elements e .. e+VW-1 of the tile, given the head state in `s`.
 //
-// With one group (K <= 8) the server update comes first: it needs every
-// gradient of the tile, so all loads have been waited for before the first
-// store is issued.  The 128-bit "sc1 nt" stores are inline assembly that the
-// compiler does not count when it forms s_waitcnt, so a wait for a load placed
-// after such a store would also wait for the store's acknowledgement; and
-// left to itself the scheduler then also sinks late gradient loads below
-// arithmetic on early ones (16-bit gradient kernels: 5.85 instead of 6.39 TB/s).
-template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF, bool NT, int VW>
+// The server update comes first: it needs every gradient of the tile, so all
+// loads have been waited for before the first store is issued.  The 128-bit
+// "sc1 nt" stores are inline assembly that the compiler does not count when it
+// forms s_waitcnt, so a wait for a load placed after such a store would also
+// wait for the store's acknowledgement; and left to itself the scheduler then
+// also sinks late gradient loads below arithmetic on early ones (16-bit
+// gradient kernels: 5.85 instead of 6.39 TB/s).
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, bool NT, int VW>
 __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ssd_gvec<GD, 4>::ptr (&gp)[K],
                                            gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t WS,
-                                           unsigned e, const ssd_head_regs<G, VW> &s)
+                                           unsigned e, const ssd_head_regs<K, VW> &s)
 {
     typedef ssd_vec<VW, NT> V;
-    constexpr int NG = (K + G - 1) / G;
-    ssd_group_regs<G, VW> cur = s.grp;
-    float w[VW], S[VW], wn[VW], mn[VW];
-    ssd_load_g<K, GD, G, NT, VW>(0, gp, e, cur);
+    float g[K][VW], w[VW], S[VW], wn[VW], mn[VW];
+#pragma unroll
+    for (int i = 0; i < K; ++i) ssd_gvec<GD, VW, NT>::ld(gp[i] + e, g[i]);
     V::ld(wp + e, w);
 
+    // Eq. (server): the sum of the K gradients, in worker order
 #pragma unroll
-    for (int j = 0; j < NG; ++j) {
-        ssd_group_regs<G, VW> nxt = {};
-        if (PF && j + 1 < NG) {
-            ssd_load_wl<K, STAGE, FG, G, NT, VW>(j + 1, wlp, WS, e, nxt);
-            ssd_load_g<K, GD, G, NT, VW>(j + 1, gp, e, nxt);
-        }
-        // Eq. (server): the sum of the K gradients, in worker order
+    for (int i = 0; i < K; ++i) {
 #pragma unroll
-        for (int i = 0; i < G; ++i) {
-            if (j * G + i < K) {
-#pragma unroll
-                for (int v = 0; v < VW; ++v) S[v] = (j * G + i == 0) ? cur.g[i][v] : S[v] + cur.g[i][v];
-            }
-        }
-        if (NG == 1) {
-            // the whole tile is here: server update first, then nothing waits any more
-#pragma unroll
-            for (int v = 0; v < VW; ++v) ssd_server_elem(S[v], w[v], s.mo[v], h, wn[v], mn[v]);
-            V::st(momp + e, mn);
-            V::st(wp + e, wn);
-        }
-        if (STAGE == SSD_STAGE_DELAY) {
-            // FG: every w'_i is the global weight as it stood before this
-            // iteration's server update (after a Pull, or at the end of warm-up),
-            // which is in registers already; the w' arrays are not read.
-            // Alg. 2: pre_weight takes w' as it was before this update.
-            if (j == 0 && PRE != SSD_PRE_KEEP) V::st(prep + e, FG ? w : cur.wl[0]);
-#pragma unroll
-            for (int i = 0; i < G; ++i) {
-                if (j * G + i < K) {
-                    float r[VW];
-#pragma unroll
-                    for (int v = 0; v < VW; ++v) {
-                        const float wli = FG ? w[v] : cur.wl[i][v];
-                        const float pv = (PRE == SSD_PRE_INIT) ? wli : s.p[v];
-                        r[v] = ssd_glu_elem<XW>(cur.g[i][v], wli, pv, h);
-                    }
-                    V::st(wlp + (int64_t)(j * G + i) * WS + e, r);
-                }
-            }
-        }
-        if (!PF && j + 1 < NG) {
-            ssd_load_wl<K, STAGE, FG, G, NT, VW>(j + 1, wlp, WS, e, nxt);
-            ssd_load_g<K, GD, G, NT, VW>(j + 1, gp, e, nxt);
-        }
-        if (j + 1 < NG) cur = nxt;
+        for (int v = 0; v < VW; ++v) S[v] = (i == 0) ? g[i][v] : S[v] + g[i][v];
     }
-
-    if (NG > 1) {
 #pragma unroll
-        for (int v = 0; v < VW; ++v) ssd_server_elem(S[v], w[v], s.mo[v], h, wn[v], mn[v]);
-        V::st(momp + e, mn);
-        V::st(wp + e, wn);
+    for (int v = 0; v < VW; ++v) ssd_server_elem(S[v], w[v], s.mo[v], h, wn[v], mn[v]);
+    V::st(momp + e, mn);
+    V::st(wp + e, wn);
+
+    if (STAGE == SSD_STAGE_DELAY) {
+        // FG: every w'_i is the global weight as it stood before this
+        // iteration's server update (after a Pull, or at the end of warm-up),
+        // which is in registers already; the w' arrays are not read.
+        // Alg. 2: pre_weight takes w' as it was before this update.
+        if (PRE != SSD_PRE_KEEP) V::st(prep + e, FG ? w : s.wl[0]);
+#pragma unroll
+        for (int i = 0; i < K; ++i) {
+            float r[VW];
+#pragma unroll
+            for (int v = 0; v < VW; ++v) {
+                const float wli = FG ? w[v] : s.wl[i][v];
+                const float pv = (PRE == SSD_PRE_INIT) ? wli : s.p[v];
+                r[v] = ssd_glu_elem<XW>(g[i][v], wli, pv, h);
+            }
+            V::st(wlp + (int64_t)i * WS + e, r);
+        }
     }
 }
 
@@ -175,24 +116,24 @@ __device__ __forceinline__ void ssd_finish(const ssd_hyper &h, const typename ss
 // the 128-bit path; a lane at a ragged end of the block, or any lane when a
 // caller pointer is not 16-byte aligned, goes element by element -- in both
 // cases with the head state preloaded in `s`.
-template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF, bool NT>
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, bool NT>
 __device__ __forceinline__ void ssd_tile(const ssd_hyper &h, const typename ssd_gvec<GD, 4>::ptr (&gp)[K],
                                          gfloat *wp, gfloat *momp, gfloat *prep, gfloat *wlp, int64_t WS,
                                          unsigned e0, unsigned lo, unsigned len, bool vec,
-                                         const ssd_head_regs<G, 4> &s)
+                                         const ssd_head_regs<K, 4> &s)
 {
     if (vec && e0 >= lo && e0 + 3 < len) {
-        ssd_finish<K, GD, STAGE, PRE, FG, XW, G, PF, NT, 4>(h, gp, wp, momp, prep, wlp, WS, e0, s);
+        ssd_finish<K, GD, STAGE, PRE, FG, XW, NT, 4>(h, gp, wp, momp, prep, wlp, WS, e0, s);
     } else if (e0 + 3 >= lo && e0 < len) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             if (e0 + v >= lo && e0 + v < len) {
-                ssd_head_regs<G, 1> s1;
+                ssd_head_regs<K, 1> s1;
                 s1.mo[0] = s.mo[v];
                 s1.p[0] = s.p[v];
 #pragma unroll
-                for (int i = 0; i < G; ++i) s1.grp.wl[i][0] = s.grp.wl[i][v];
-                ssd_finish<K, GD, STAGE, PRE, FG, XW, G, false, NT, 1>(h, gp, wp, momp, prep, wlp, WS, e0 + v, s1);
+                for (int i = 0; i < K; ++i) s1.wl[i][0] = s.wl[i][v];
+                ssd_finish<K, GD, STAGE, PRE, FG, XW, NT, 1>(h, gp, wp, momp, prep, wlp, WS, e0 + v, s1);
             }
         }
     }
@@ -201,7 +142,7 @@ __device__ __forceinline__ void ssd_tile(const ssd_hyper &h, const typename ssd_
 // The arguments a wave needs first come as separate leading kernel arguments
 // so that they can be preloaded into scalar registers at wave launch
 // (-amdgpu-kernarg-preload-count); the rest arrives with ordinary scalar loads.
-template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, int G, bool PF, bool NT>
+template <int K, int GD, int STAGE, int PRE, bool FG, bool XW, bool NT>
 __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *block_tensor, float *mom,
                                                               float *pre, float *wl, int64_t A,
                                                               unsigned C, unsigned blocks_per_xcd,
@@ -220,8 +161,8 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
     constexpr bool IL = ssd_interleave_of(K);
     gfloat *wlp = ssd_global(wl) + (IL ? ao * K : ao);
     const int64_t WS = IL ? (int64_t)C : A; // from worker i's copy of the block to worker i+1's
-    ssd_head_regs<G, 4> s;
-    ssd_load_head<K, STAGE, PRE, FG, G, NT, 4>(momp, prep, wlp, WS, lane * 4, s);
+    ssd_head_regs<K, 4> s;
+    ssd_load_head<K, STAGE, PRE, FG, NT, 4>(momp, prep, wlp, WS, lane * 4, s);
 
     // block -> tensor -> one record {w, elem0, numel, g_0 .. g_{K-1}}
     // and the tensor's hyper-parameters
@@ -245,10 +186,10 @@ __global__ __launch_bounds__(SSD_BLOCK) void ssd_fused_kernel(const int32_t *blo
 
     unsigned base = 0;
     for (;;) {
-        ssd_tile<K, GD, STAGE, PRE, FG, XW, G, PF, NT>(h, gp, wp, momp, prep, wlp, WS, base + lane * 4, lo, len, vec, s);
+        ssd_tile<K, GD, STAGE, PRE, FG, XW, NT>(h, gp, wp, momp, prep, wlp, WS, base + lane * 4, lo, len, vec, s);
         base += SSD_BLOCK * 4;
         if (base >= len) break; // uniform
-        ssd_load_head<K, STAGE, PRE, FG, G, NT, 4>(momp, prep, wlp, WS, base + lane * 4, s);
+        ssd_load_head<K, STAGE, PRE, FG, NT, 4>(momp, prep, wlp, WS, base + lane * 4, s);
     }
 }
 
@@ -279,8 +220,6 @@ hipError_t SSD_CAT(SSD_CAT(SSD_CAT(ssd_launch_fused_g, SSD_GD), _k), SSD_K)(int 
                                                const ssd_fused_args &a)
 {
     const dim3 grid(nchunks), block(SSD_BLOCK);
-    constexpr int G = ssd_group_of(SSD_K);
-    constexpr bool PF = ssd_prefetch_of(SSD_K);
     // lds_bytes: the occupancy cap, a slice of LDS that is never accessed
 #define SSD_GO(ST, PR, FG, XW)                                                                     \
     do {                                                                                           \
@@ -289,7 +228,7 @@ hipError_t SSD_CAT(SSD_CAT(SSD_CAT(ssd_launch_fused_g, SSD_GD), _k), SSD_K)(int 
     } while (0)
 #define SSD_GO_NT(ST, PR, FG, XW, NT)                                                              \
     do {                                                                                           \
-        auto kernel = ssd_fused_kernel<SSD_K, SSD_GD, ST, PR, FG, XW, G, PF, NT>;                  \
+        auto kernel = ssd_fused_kernel<SSD_K, SSD_GD, ST, PR, FG, XW, NT>;                         \
         if (lds_bytes > 65536) {                                                                   \
             static std::atomic<unsigned long long> done{0};                                        \
             const hipError_t e = ssd_allow_lds(kernel, lds_limit, done);                           \

@@ -432,14 +432,6 @@ int ssd_lds_slice_bytes(int32_t waves_per_cu, int32_t lds_bytes_per_cu)
     return (128 / waves_per_cu) * granule;
 }
 
-int ssd_fused_variant(int32_t num_workers, int32_t *group, int32_t *prefetch)
-{
-    if (num_workers < 1 || num_workers > SSD_MAX_WORKERS) return SSD_EINVAL;
-    if (group) *group = ssd_group_of(num_workers);
-    if (prefetch) *prefetch = ssd_prefetch_of(num_workers) ? 1 : 0;
-    return SSD_OK;
-}
-
 int ssd_config_defaults(ssd_config *cfg, int32_t num_workers, float lr, float wd)
 {
     if (!cfg) return fail_init(SSD_EINVAL, "cfg is NULL");
@@ -722,26 +714,23 @@ static int check_grads(ssd_ctx *c, const void *const *const *grads)
 
 // Resident waves per compute unit that gave the highest HBM throughput when
 // measured on MI355X: sweeps over 2..16 waves for K = 1, 2, 4, 8 on 133-138 M-
-// element models and K = 16 on a 60 M-element one, with binary32 and with
-// bfloat16 gradient buffers.  Up to K = 8 (a wave requests its whole tile at
-// once) the best cap falls as a wave carries more streams, roughly as
+// element models and K = 9 ... 16 on a 60 M-element one, with binary32 and with
+// bfloat16 gradient buffers.  A wave requests its whole tile at once, so the
+// best cap falls as a wave carries more streams, roughly as
 // budget / (loads per lane), and is flat within +-1:
 //   plain delay kernel   58 / (2K + 3), at least 4   (K = 8: 4, K = 2: 8)
 //   from-global kernel   44 / (K + 3),  at least 4   (50 with 16-bit gradients)
 //   warm-up kernel       58 / (K + 2),  at least 6   (read-dominated: its
 //                        16-bit gradient loads count half, budget 52)
-// Beyond K = 8 a wave takes the workers in groups of 4, two groups requested
-// at a time, so its loads in flight no longer grow with K; measured at K = 9,
-// 10, 12, 14, 16: 4 waves for the plain kernel (5 at K = 9), 6 for the
-// from-global and the warm-up kernel (which have no local weights to read, so
-// half the loads in flight); with 16-bit gradients (half-size gradient loads;
-// K = 16) 5, 6 and 8.
+// Beyond K = 8 the K local weights of a tile are one contiguous piece
+// (ssd_interleave_of), which moves the optimum of the plain kernel down to 3
+// waves for every K = 9 ... 16 (4 waves: -3 ... -8 %); the other two kernels
+// do not read the local weights and stay at 4 and 6 (8 with 16-bit gradients).
 static int default_waves_per_cu(int K, int stage, int from_global, bool grad16)
 {
     if (K > 8) {
         if (stage == SSD_STAGE_WARMUP) return grad16 ? 8 : 6;
-        if (from_global) return 6;
-        return (grad16 || K == 9) ? 5 : 4;
+        return from_global ? 4 : 3;
     }
     int loads2, budget, floor_n; // loads per lane in halves of a 128-bit load
     if (stage == SSD_STAGE_WARMUP)

@@ -33,12 +33,12 @@ def test_misaligned_pointers_take_scalar_path(w_shift, g_shift):
 
 
 @pytest.mark.parametrize("K,w_shift,g_shift", [(9, 0, 1), (11, 1, 2), (16, 3, 0), (16, 0, 0)])
-def test_grouped_kernels_on_the_scalar_path_and_large_chunks(K, w_shift, g_shift):
-    """K > 8: the wave takes the workers in groups (the last group partial for
-    K = 9, 11).  Misaligned caller pointers send every lane element by element
-    through all groups; chunks of several tiles loop over the groups per tile;
-    the exact-w_minus variant is its own kernel."""
-    print("case: groups K=%d w_shift=%d g_shift=%d" % (K, w_shift, g_shift), flush=True)
+def test_more_than_8_workers_on_the_scalar_path_and_large_chunks(K, w_shift, g_shift):
+    """K > 8: the local weights are interleaved by block.  Misaligned caller
+    pointers send every lane element by element; chunks of several tiles make
+    the interleaved unit larger than a tile; the exact-w_minus variant is its
+    own kernel."""
+    print("case: more than 8 workers K=%d w_shift=%d g_shift=%d" % (K, w_shift, g_shift), flush=True)
     run_schedule(ODD, K=K, k=3, W=1, steps=1 + 7, w_shift=w_shift, g_shift=g_shift, seed=100 + K)
     run_schedule([20000, 8193, 7], K=K, k=2, W=0, steps=5, chunk_elems=1024, w_shift=w_shift, g_shift=g_shift,
                  seed=200 + K, hp=dict(lr=0.1, momentum=0.9, wd=1e-4, grad_sync_exact=1))
