@@ -50,9 +50,10 @@ static float rnd(void) /* xorshift, uniform in (-1, 1) */
     return (float)((double)(rng_state >> 11) / 4503599627370496.0 - 1.0);
 }
 
-enum { T = 3, K = 3, STEPS = 7, P = 2 };
+enum { T = 3, KMAX = 9, STEPS = 7, P = 2 };
 
-int main(void)
+/* K = 3: planar local-weight arrays; K = 9: interleaved by block (see ssd_state_view) */
+static int run(const int K)
 {
     const int64_t numel[T] = {1000, 37, 4101};
     long N = 0, off[T + 1];
@@ -61,7 +62,7 @@ int main(void)
     ssd_ctx *ctx = NULL;
 
     /* host copies: w0 and P sets of K gradients, flat in tensor order */
-    float *w0 = malloc(sizeof(float) * N), *g[P][K];
+    float *w0 = malloc(sizeof(float) * N), *g[P][KMAX];
     for (long j = 0; j < N; ++j) w0[j] = rnd();
     for (int p = 0; p < P; ++p)
         for (int i = 0; i < K; ++i) {
@@ -70,7 +71,7 @@ int main(void)
         }
 
     /* device copies: one allocation per tensor, as a framework would hand them over */
-    float *d_w[T], *d_g[P][K][T];
+    float *d_w[T], *d_g[P][KMAX][T];
     for (int t = 0; t < T; ++t) {
         CK(hipMalloc((void **)&d_w[t], sizeof(float) * numel[t]));
         CK(hipMemcpy(d_w[t], w0 + off[t], sizeof(float) * numel[t], hipMemcpyHostToDevice));
@@ -112,9 +113,9 @@ int main(void)
 
     for (int it = 0; it < STEPS; ++it) {
         const int p = it % P;
-        const float *rows[K][T];
-        const void *const *grads[K];
-        const float *og[K];
+        const float *rows[KMAX][T];
+        const void *const *grads[KMAX];
+        const float *og[KMAX];
         for (int i = 0; i < K; ++i) {
             for (int t = 0; t < T; ++t) rows[i][t] = d_g[p][i][t];
             grads[i] = (const void *const *)rows[i];
@@ -138,7 +139,7 @@ int main(void)
         CK(hipMemcpy(buf, v.pre + v.tensor_offset[t], sizeof(float) * numel[t], hipMemcpyDeviceToHost));
         bad += memcmp(buf, o.pre + off[t], sizeof(float) * numel[t]) != 0;
         for (int i = 0; i < K; ++i) {
-            /* w'_i block by block: the general addressing of ssd_state_view (planar for this K) */
+            /* w'_i block by block: the general addressing of ssd_state_view */
             for (int64_t a = v.tensor_offset[t], end = a + numel[t]; a < end;) {
                 const int64_t blk = a / v.chunk_elems, pos = a % v.chunk_elems;
                 const int64_t n = end - a < v.chunk_elems - pos ? end - a : v.chunk_elems - pos;
@@ -151,13 +152,20 @@ int main(void)
         }
     }
     /* error path: a NULL gradient pointer is refused and leaves the state alone */
-    const void *const *nullgrads[K] = {NULL, NULL, NULL};
+    const void *const *nullgrads[KMAX] = {NULL};
     if (ssd_step(ctx, nullgrads) != SSD_EINVAL) bad += 1000;
     if (v.iterations != STEPS) bad += 10000;
     ssd_destroy(ctx);
     if (bad)
         printf("C ABI demo: MISMATCH (%ld)\n", bad);
     else
-        printf("C ABI demo: OK, %d iterations bit-identical to the oracle\n", (int)STEPS);
+        printf("C ABI demo: OK, K = %d, %d iterations bit-identical to the oracle\n", K, (int)STEPS);
     return bad ? 1 : 0;
+}
+
+int main(void)
+{
+    int rc = run(3);
+    if (rc == 0) rc = run(KMAX);
+    return rc;
 }

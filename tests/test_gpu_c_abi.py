@@ -16,4 +16,4 @@ def test_c_program_drives_the_library():
     print("case: C ABI demo", flush=True)
     r = subprocess.run([EXE], capture_output=True, text=True, timeout=120)
     print(r.stdout, r.stderr)
-    assert r.returncode == 0 and "OK" in r.stdout
+    assert r.returncode == 0 and "OK, K = 3," in r.stdout and "OK, K = 9," in r.stdout
