@@ -243,6 +243,26 @@ bool fits_last_level_cache(const ssd_config &c, const Layout &L)
     return (size_t)L.A * per_elem <= kLastLevelCacheBytes;
 }
 
+// Distance in bytes between consecutive state arrays of `bytes` bytes each.
+// Large arrays are placed a multiple of 64 MiB (2 MiB for mid-sized ones)
+// apart: with the dozens of streams of the fused kernel walking all arrays at
+// the same relative position, that placement measured 2-7 % more HBM
+// throughput on MI355X than arbitrary distances (K = 8 and 16, 100-550 MB
+// arrays) -- but not a multiple of 256 MiB: distances of 256, 512 and 768 MiB
+// measured 3-6 % less than 384, 640 and 896 MiB on the same models (K = 4 and
+// 8; 61 M- to 198 M-element models), so those take two more units.
+size_t array_distance(size_t bytes)
+{
+    size_t arr = round_up(bytes, kWsAlign);
+    if (arr >= ((size_t)64 << 20)) {
+        arr = round_up(arr, (size_t)64 << 20);
+        if (arr % ((size_t)256 << 20) == 0) arr += (size_t)128 << 20;
+    } else if (arr >= ((size_t)2 << 20)) {
+        arr = round_up(arr, (size_t)2 << 20);
+    }
+    return arr;
+}
+
 // weights == nullptr: sizes for the worst case over all weight alignments
 // (what ssd_workspace_bytes reports before the pointers are known).
 int make_layout(const ssd_config *c, float *const *weights, Layout *L)
@@ -267,16 +287,17 @@ int make_layout(const ssd_config *c, float *const *weights, Layout *L)
     const int64_t a = blocks * L->chunk_elems; // blocks == num_chunks
     L->A = a;
     size_t o = 0;
-    // Distance between consecutive state arrays.  Large arrays are placed a
-    // multiple of 64 MiB (2 MiB for mid-sized ones) apart: with the dozens of
-    // streams of the fused kernel walking all arrays at the same relative
-    // position, that placement measured 2-7 % more HBM throughput on MI355X
-    // than arbitrary distances (K = 8 and 16, 100-550 MB arrays).
-    size_t arr = round_up(sizeof(float) * (size_t)a, kWsAlign);
-    if (arr >= ((size_t)64 << 20))
-        arr = round_up(arr, (size_t)64 << 20);
-    else if (arr >= ((size_t)2 << 20))
-        arr = round_up(arr, (size_t)2 << 20);
+    size_t arr = array_distance(sizeof(float) * (size_t)a);
+    if (!weights) {
+        // worst case over the alignments: the rule is not monotone, so every
+        // arena size between the one without lead-ins and this one counts
+        int64_t blocks_min = 0;
+        for (int t = 0; t < T; ++t) blocks_min += (c->numel[t] + L->chunk_elems - 1) / L->chunk_elems;
+        const size_t unit = (size_t)64 << 20;
+        const size_t lo = sizeof(float) * (size_t)blocks_min * L->chunk_elems, hi = sizeof(float) * (size_t)a;
+        arr = std::max(arr, array_distance(lo));
+        for (size_t x = round_up(lo, unit); x < hi; x += unit) arr = std::max(arr, array_distance(x));
+    }
     L->stride = (int64_t)(arr / sizeof(float));
     L->off_mom = o, o += arr;
     if (c->delay_k > 0) {

@@ -259,3 +259,33 @@ def test_config_defaults_follow_the_papers_settings():
     assert (m.lr_loc, m.alpha, m.beta, m.rescale_grad) == (np.float32(1.6), 2.0, 0.5, 0.25)
     m = B.make_config([10], 4, 2, 1, 0.4, 0.9, 1e-4, lr_loc=1.0, alpha=1.0, beta=0.0, wd_loc=0.0, rescale_grad=1.0)
     assert (m.lr_loc, m.alpha, m.beta, m.wd_loc, m.rescale_grad) == (1.0, 1.0, 0.0, 0.0, 1.0)
+
+
+def test_state_arrays_are_never_a_multiple_of_256_mib_apart():
+    """The distance between consecutive state arrays, read off the workspace
+    size (one more worker adds a w' and a w_loc array): a multiple of 64 MiB for
+    large arrays, and never a multiple of 256 MiB."""
+    MiB = 1 << 20
+    for n, expect in ((60192808, 384 * MiB),      # 229.6 MiB -> 256 -> 384
+                      (138357544, 576 * MiB),     # 527.8 MiB -> 576
+                      (132863336, 640 * MiB),     # 506.8 MiB -> 512 -> 640
+                      (25557032, 128 * MiB),      # 97.5 MiB -> 128
+                      (198000000, 896 * MiB)):    # 755.3 MiB -> 768 -> 896
+        a = B.ssd_workspace_bytes(_cfg(numel=[n], K=3, k=2))
+        b = B.ssd_workspace_bytes(_cfg(numel=[n], K=4, k=2))
+        # pointer tables grow by a few hundred bytes per worker
+        assert 0 <= (b - a) - 2 * expect < 4096, (n, (b - a) / MiB)
+
+
+def test_workspace_bound_holds_where_the_array_distance_jumps():
+    """One tensor of 256 MiB - 512 B: laid out from a 1 KiB-aligned weight
+    pointer its arena is exactly 256 MiB, which the library spaces 384 MiB
+    apart; with a lead-in it is one block more, spaced 320 MiB.  The size
+    quoted before the pointers are known must cover both."""
+    n = (256 << 20) // 4 - 128
+    cfg = _cfg(numel=[n], K=2, k=2)
+    bound = B.ssd_workspace_bytes(cfg)
+    for addr in (1 << 30, (1 << 30) + 16, (1 << 30) + 1008, (1 << 30) + 4):
+        _, blocks, nbytes = B.ssd_plan_arena(cfg, [addr])
+        assert nbytes <= bound, (addr, nbytes, bound)
+    assert B.ssd_plan_arena(cfg, [1 << 30])[2] > B.ssd_plan_arena(cfg, [(1 << 30) + 1008])[2]
