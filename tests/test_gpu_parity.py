@@ -78,11 +78,14 @@ def test_lead_in_of_large_tensors(K, w_shift, g_shift, chunk):
     ctx.close()
 
 
-def test_lead_in_piecewise_equals_fused():
-    print("case: lead-in, piecewise", flush=True)
+@pytest.mark.parametrize("K", [3, 11])
+def test_lead_in_piecewise_equals_fused(K):
+    """Piecewise calls on tensors with lead-ins; K = 11: the GLU and Pull kernels
+    walk the interleaved local weights with their block stride."""
+    print("case: lead-in, piecewise K=%d" % K, flush=True)
     from oracle.ssd_oracle import Oracle
     from paper_2012_05396_amd import binding as B
-    K, k, W = 3, 2, 1
+    k, W = 2, 1
     m = Model(BIG, K, seed=55)
     ctx = B.Context(B.make_config(BIG, K, k, W, 0.1, 0.9, 1e-4, stream=torch.cuda.current_stream().cuda_stream),
                     m.weights)
