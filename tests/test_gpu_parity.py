@@ -501,3 +501,34 @@ def test_randomized_configurations(seed):
         seed, K, k, W, numel, hp, w_shift, g_shift, chunk), flush=True)
     run_schedule(numel, K=K, k=k, W=W, steps=steps, hp=hp, seed=seed, w_shift=w_shift, g_shift=g_shift,
                  chunk_elems=chunk)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_randomized_configurations(seed):
+    """Seeded random draws over everything a configuration can combine: worker
+    count (planar and interleaved local weights), delay, warm-up length, tensor
+    sizes around the tile, lead-in and block boundaries, pointer misalignment,
+    block size, gradient element type, exact w_minus, hyper-parameters and a
+    learning-rate change -- each against the oracle, bit for bit, with both
+    cache policies side by side."""
+    rng = np.random.default_rng(1000 + seed)
+    K = int(rng.choice([1, 2, 3, 5, 7, 8, 9, 10, 13, 16]))
+    k = int(rng.choice([1, 2, 3, 5]))
+    W = int(rng.choice([0, 1, 2]))
+    sizes = [int(rng.choice([1, 3, 4, 63, 255, 256, 257, 1000, 4099, 8191, 8192, 8193, 9000, 20001]))
+             for _ in range(int(rng.integers(1, 7)))]
+    w_shift = int(rng.choice([0, 0, 0, 1, 4, 8]))
+    g_shift = int(rng.choice([0, 0, 0, 2, 4, 12]))
+    chunk = int(rng.choice([0, 256, 512, 1024]))
+    gd = int(rng.choice([0, 0, 1, 2]))
+    if gd:                       # 16-bit buffers: shifts in elements of 2 bytes, keep them even for 4-byte alignment
+        g_shift -= g_shift % 2
+    hp = dict(lr=float(rng.choice([0.1, 0.05])), momentum=float(rng.choice([0.9, 0.5])), wd=float(rng.choice([1e-4, 0.0])),
+              alpha=float(rng.choice([2.0, 1.0])), beta=float(rng.choice([0.5, 0.25])),
+              grad_sync_exact=int(rng.integers(0, 2)))
+    steps = W + 2 * k + int(rng.integers(1, 4))
+    lr_changes = {int(rng.integers(1, steps)): (0.03, 0.2)} if rng.integers(0, 2) else None
+    print("case: random seed=%d K=%d k=%d W=%d sizes=%s w_shift=%d g_shift=%d chunk=%d gd=%d hp=%s lr_changes=%s"
+          % (seed, K, k, W, sizes, w_shift, g_shift, chunk, gd, hp, lr_changes), flush=True)
+    run_schedule(sizes, K=K, k=k, W=W, steps=steps, hp=hp, chunk_elems=chunk, seed=seed, w_shift=w_shift,
+                 g_shift=g_shift, grad_dtype=gd, lr_changes=lr_changes, P=2)
